@@ -1,0 +1,241 @@
+"""CPU oracle for the QJL key-cache hot path.  TEST INFRASTRUCTURE ONLY.
+
+This module is a plain, slow, float64 restatement of what the QJL paper
+(arXiv 2406.03482) defines.  It exists so that the GPU library can be checked
+against something that is obviously the paper's mathematics.  Nothing in the
+product path may import it: only the tests, the smoke check and the
+`cpu_baseline` leg of the benchmark do.  It shares no code, table, constant
+generator or helper with the HIP library.
+
+Every function names the passage it follows:
+
+  * Definition 3.1, Eq. (3)      H_S(k) = sign(S k)
+  * Definition 3.1, Eq. (4)      Prod_QJL(q,k) = sqrt(pi/2)/m * ||k||_2 * <S q, H_S(k)>
+  * Algorithm 1, steps 1-4       draw S; per key store sign(S k) and nu = ||k||_2
+  * Algorithm 1, EstimateScores  estimator for every cached key, then softmax
+  * Section 2, Eq. (1), (2)      o_n = sum_i Score(i) v_i ,  Score = softmax(.)
+
+Readings of points the paper leaves open (all restated where they are used):
+
+  * sign(0) := +1, i.e. bit 1 iff the projection is >= 0 (the codomain of
+    H_S is {-1,+1}, so zero needs a side).
+  * Packing: projection i of a key lives in byte i//8, bit i%8 (LSB first);
+    bit 1 <-> +1.
+  * Algorithm 1 prints nu_i inside a formula indexed by j; it is nu_j, the
+    norm of the key whose code is being used (as in Eq. (4)).
+  * The norm is stored in IEEE binary16 (round-to-nearest-even), and the
+    score estimator uses that stored value.
+  * Eq. (2) has no 1/sqrt(d); a `scale` factor multiplies the estimator
+    before the softmax, and scale = 1 is the paper's literal definition.
+  * Grouped-query attention: query head h reads the cache of key/value head
+    h // (Hq // Hkv).
+  * The sketch S is data: Algorithm 1 step 1 only asks for i.i.d. N(0,1)
+    entries.  `gaussian_sketch` fixes one reproducible way to draw them
+    (SplitMix64 counter -> Box-Muller in float64 -> rounding to the storage
+    type).  Its exact values are pinned by a published SplitMix64 test
+    vector, by determinism and by distribution tests only: beyond that the
+    *values* of S are "parity unpinned" (any i.i.d. N(0,1) matrix is a valid
+    S).  Every other function here is pinned by tests/test_oracle_pins.py.
+
+Array conventions (all dense, C order):
+    K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
+    bits  [B, Hkv, n, m/8]   nu  [B, Hkv, n]     SQ     [B, Hq, m]
+    scores[B, Hq, n]         out [B, Hq, d]
+Inputs that were stored in bf16/fp16/fp32 are passed in already converted,
+exactly, to float64.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+SQRT_HALF_PI = math.sqrt(math.pi / 2.0)
+
+_MASK64 = (1 << 64) - 1
+_GOLDEN = 0x9E3779B97F4A7C15
+_MIX1 = 0xBF58476D1CE4E5B9
+_MIX2 = 0x94D049BB133111EB
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1, step 1: the sketch
+# --------------------------------------------------------------------------
+def splitmix64_at(seed: int, counter: np.ndarray) -> np.ndarray:
+    """The `counter`-th output (0-based) of the SplitMix64 stream started at
+    `seed` (Steele, Lea, Flood 2014): state = seed + (counter+1)*golden, then
+    the two xor-shift-multiply rounds and a final xor-shift."""
+    c = np.asarray(counter, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        z = np.uint64(seed & _MASK64) + (c + np.uint64(1)) * np.uint64(_GOLDEN)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(_MIX1)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(_MIX2)
+        z = z ^ (z >> np.uint64(31))
+    return z
+
+
+def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float64 values to the storage type and return them as float64.
+    f32: one RNE rounding.  f16 / bf16: RNE to float32 first, then RNE to the
+    16-bit type (the same two steps a float32 pipeline performs)."""
+    x32 = np.asarray(x, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return x32.astype(np.float64)
+    if dtype == "f16":
+        return x32.astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        u = x32.view(np.uint32).astype(np.uint64)
+        lsb = (u >> np.uint64(16)) & np.uint64(1)
+        u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+        return u.astype(np.uint32).view(np.float32).astype(np.float64)
+    raise ValueError(f"unknown storage dtype {dtype!r}")
+
+
+def gaussian_sketch(seed: int, m: int, d: int, dtype: str = "f32") -> np.ndarray:
+    """Algorithm 1 step 1 / Definition 3.1: S in R^{m x d}, i.i.d. N(0,1).
+
+    Entry e = i*d + j uses SplitMix64 outputs 2e and 2e+1 of the stream
+    `seed`:  U1 = ((a >> 11) + 1) / 2^53 in (0,1],  U2 = (b >> 11) / 2^53 in
+    [0,1),  z = sqrt(-2 ln U1) * cos(2 pi U2)  (Box-Muller, float64), then
+    `round_to_storage`.
+    """
+    e = np.arange(m * d, dtype=np.uint64)
+    a = splitmix64_at(seed, np.uint64(2) * e)
+    b = splitmix64_at(seed, np.uint64(2) * e + np.uint64(1))
+    u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * 2.0 ** -53
+    u2 = (b >> np.uint64(11)).astype(np.float64) * 2.0 ** -53
+    z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    return round_to_storage(z, dtype).reshape(m, d)
+
+
+# --------------------------------------------------------------------------
+# Definition 3.1 Eq. (3) and Algorithm 1 steps 3-4: quantize keys
+# --------------------------------------------------------------------------
+def key_projections(K: np.ndarray, S: np.ndarray) -> np.ndarray:
+    """P[..., j, i] = <s_i, k_j> = (S k_j)_i in float64 (Eq. (3) before sign)."""
+    K = np.asarray(K, dtype=np.float64)
+    S = np.asarray(S, dtype=np.float64)
+    return np.einsum("...jt,it->...ji", K, S)
+
+
+def pack_sign_bits(nonneg: np.ndarray) -> np.ndarray:
+    """Pack a boolean array [..., m] (True <-> +1) into uint8 [..., m/8]:
+    projection i -> byte i//8, bit i%8."""
+    nonneg = np.asarray(nonneg, dtype=bool)
+    m = nonneg.shape[-1]
+    if m % 8:
+        raise ValueError("m must be a multiple of 8")
+    grouped = nonneg.reshape(nonneg.shape[:-1] + (m // 8, 8)).astype(np.uint16)
+    out = np.zeros(grouped.shape[:-1], dtype=np.uint16)
+    for t in range(8):
+        out |= grouped[..., t] << t
+    return out.astype(np.uint8)
+
+
+def unpack_signs(bits: np.ndarray, m: int) -> np.ndarray:
+    """Inverse of `pack_sign_bits`, returned as float64 values in {-1,+1}."""
+    bits = np.asarray(bits, dtype=np.uint8)
+    if bits.shape[-1] * 8 != m:
+        raise ValueError("bits last dim must be m/8")
+    sig = np.empty(bits.shape[:-1] + (m,), dtype=np.float64)
+    for t in range(8):
+        sig[..., t::8] = ((bits >> t) & 1).astype(np.float64) * 2.0 - 1.0
+    return sig
+
+
+def key_norms(K: np.ndarray) -> np.ndarray:
+    """nu_j = ||k_j||_2 (Algorithm 1 step 3) in float64, stored as binary16."""
+    K = np.asarray(K, dtype=np.float64)
+    return np.sqrt(np.sum(K * K, axis=-1)).astype(np.float16)
+
+
+def quantize_keys(K: np.ndarray, S: np.ndarray):
+    """Algorithm 1 steps 3-4 for every key: returns (bits, nu16, P).
+
+    bits  uint8  [..., n, m/8]   packed H_S(k_j) = sign(S k_j), sign(0) = +1
+    nu16  float16[..., n]        stored key norms
+    P     float64[..., n, m]     the projections themselves (so a caller can
+                                 see how close to zero a sign decision was)
+    """
+    P = key_projections(K, S)
+    return pack_sign_bits(P >= 0.0), key_norms(K), P
+
+
+# --------------------------------------------------------------------------
+# Definition 3.1 Eq. (4) and Algorithm 1 EstimateScores
+# --------------------------------------------------------------------------
+def project_query(Q: np.ndarray, S: np.ndarray) -> np.ndarray:
+    """SQ[b,h,:] = S q  -- the query side of Eq. (4), not quantized."""
+    Q = np.asarray(Q, dtype=np.float64)
+    S = np.asarray(S, dtype=np.float64)
+    return np.einsum("...t,it->...i", Q, S)
+
+
+def estimate_scores(SQ: np.ndarray, bits: np.ndarray, nu16: np.ndarray,
+                    scale: float = 1.0) -> np.ndarray:
+    """scale * Prod_QJL(q_h, k_j) for every query head h and cached key j:
+
+        scale * sqrt(pi/2)/m * nu_j * <S q_h, H_S(k_j)>      (Eq. (4))
+
+    SQ [B,Hq,m], bits [B,Hkv,n,m/8], nu16 [B,Hkv,n] -> [B,Hq,n].
+    """
+    SQ = np.asarray(SQ, dtype=np.float64)
+    B, Hq, m = SQ.shape
+    Hkv = bits.shape[1]
+    if Hq % Hkv:
+        raise ValueError("Hq must be a multiple of Hkv")
+    G = Hq // Hkv
+    sig = unpack_signs(bits, m)                          # [B,Hkv,n,m]
+    nu = np.asarray(nu16, dtype=np.float16).astype(np.float64)
+    out = np.empty((B, Hq, bits.shape[2]), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            inner = sig[b, g] @ SQ[b, h]                 # <S q, H_S(k_j)> for all j
+            out[b, h] = scale * (SQRT_HALF_PI / m) * nu[b, g] * inner
+    return out
+
+
+def softmax(x: np.ndarray) -> np.ndarray:
+    """softmax over the last axis (Eq. (2)), computed with the maximum
+    subtracted, which does not change its value."""
+    x = np.asarray(x, dtype=np.float64)
+    e = np.exp(x - np.max(x, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attention_from_scores(scores: np.ndarray, V: np.ndarray) -> np.ndarray:
+    """o = sum_j softmax(scores)_j v_j (Eq. (1)); scores [B,Hq,n], V
+    [B,Hkv,n,d] -> [B,Hq,d]."""
+    V = np.asarray(V, dtype=np.float64)
+    B, Hq, _ = scores.shape
+    Hkv = V.shape[1]
+    G = Hq // Hkv
+    p = softmax(scores)
+    out = np.empty((B, Hq, V.shape[-1]), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            out[b, h] = p[b, h] @ V[b, h // G]
+    return out
+
+
+def decode_attention(Q: np.ndarray, S: np.ndarray, bits: np.ndarray,
+                     nu16: np.ndarray, V: np.ndarray,
+                     scale: float = 1.0) -> np.ndarray:
+    """One decode step on a quantized key cache: project the query, estimate
+    all scores (Algorithm 1, EstimateScores), softmax, aggregate values
+    (Eq. (1))."""
+    SQ = project_query(Q, S)
+    return attention_from_scores(estimate_scores(SQ, bits, nu16, scale), V)
+
+
+def prod_qjl(q: np.ndarray, k: np.ndarray, S: np.ndarray) -> float:
+    """Eq. (4) for one pair of vectors, written straight from the definition
+    (no packing, float64 norm): used by the statistical tests of Lemma 3.2
+    and Lemma 3.5."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    S = np.asarray(S, dtype=np.float64)
+    m = S.shape[0]
+    h = np.where(S @ k >= 0.0, 1.0, -1.0)
+    return SQRT_HALF_PI / m * math.sqrt(float(k @ k)) * float((S @ q) @ h)
