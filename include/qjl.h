@@ -1,0 +1,148 @@
+/*
+ * qjl.h -- C ABI of the MI355X (gfx950) QJL key-cache library.
+ *
+ * QJL (arXiv 2406.03482) compresses the key cache of an attention layer to one
+ * sign bit per random projection plus one norm per key, and estimates
+ * query-key inner products from that code:
+ *
+ *   Definition 3.1, Eq. (3)   H_S(k) = sign(S k)                 S in R^{m x d}, i.i.d. N(0,1)
+ *   Definition 3.1, Eq. (4)   Prod_QJL(q,k) = sqrt(pi/2)/m * ||k||_2 * <S q, H_S(k)>
+ *   Algorithm 1               per key store H_S(k) and nu = ||k||_2; EstimateScores = softmax of Eq. (4)
+ *   Section 2, Eq. (1)-(2)    o = sum_j softmax(.)_j v_j
+ *
+ * General rules for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     allocates nothing and keeps no state between calls.  Tensors are dense,
+ *     row-major, with exactly the shapes stated below.  Pointers must be
+ *     16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without waiting.
+ *   - The return value is a status code; nothing throws or aborts.  Invalid
+ *     arguments are rejected on the host before anything is launched.
+ *   - Head mapping (grouped-query attention): query head h uses the keys and
+ *     values of KV head h / (q_heads / kv_heads).
+ *   - Code layout (fixed, shared by all calls): projection i of a key is bit
+ *     i%8 of byte i/8 (equivalently bit i%32 of little-endian 32-bit word
+ *     i/32); bit 1 means (S k)_i >= 0, i.e. sign +1 (sign(0) := +1).
+ *     Norms are IEEE binary16, round-to-nearest-even of the fp32 norm.
+ */
+#ifndef QJL_H_
+#define QJL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  QJL_OK = 0,
+  QJL_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, misaligned pointer, bad dtype tag */
+  QJL_ERR_UNSUPPORTED = -2, /* a valid shape this build has no kernel for (see each call) */
+  QJL_ERR_WORKSPACE = -3,   /* workspace missing or smaller than qjl_decode_workspace_bytes() */
+  QJL_ERR_HIP = -4          /* the HIP runtime reported an error at launch */
+};
+
+/* Storage type of K, Q, V and S (the paper's kernels take bf16, fp16 and fp32). */
+enum { QJL_F32 = 0, QJL_F16 = 1, QJL_BF16 = 2 };
+
+typedef struct {
+  int32_t batch;    /* B   >= 1 */
+  int32_t q_heads;  /* Hq  >= 1, a multiple of kv_heads */
+  int32_t kv_heads; /* Hkv >= 1 */
+  int32_t n;        /* number of cached keys per (batch, kv head), >= 1 */
+  int32_t d;        /* head dimension; this build: 128 */
+  int32_t m;        /* sketch dimension; this build: 128, 256 or 512 */
+  int32_t dtype;    /* QJL_F32 / QJL_F16 / QJL_BF16: type of K, Q, V and S */
+  float scale;      /* multiplies Eq. (4) before the softmax; 1.0f is Eq. (2) as printed */
+} qjl_shape;
+
+/* Library version (major*10000 + minor*100 + patch). Host only. */
+int qjl_version(void);
+
+/* Human-readable text for a status code (static storage). Host only. */
+const char* qjl_status_string(int status);
+
+/*
+ * Algorithm 1 step 1 / Definition 3.1: fill S[m,d] (device, row-major, type
+ * `dtype`) with i.i.d. N(0,1) samples that depend only on (seed, m, d, dtype):
+ * entry e = i*d+j takes outputs 2e and 2e+1 of the SplitMix64 stream `seed`,
+ * U1 = ((a>>11)+1)/2^53, U2 = (b>>11)/2^53, z = sqrt(-2 ln U1) cos(2 pi U2) in
+ * fp64, rounded to fp32 and then (for 16-bit types) to `dtype`, both RNE.
+ * The same S must be passed to the key and to the query side.
+ * Requires m >= 1, d >= 1.
+ */
+int qjl_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, void* stream);
+
+/*
+ * Algorithm 1 steps 3-4 for all keys at once (Definition 3.1 Eq. (3)):
+ *   bits [B,Hkv,n,m/8] (uint8)  <- packed sign(S k)
+ *   norms[B,Hkv,n]     (binary16 bit patterns) <- ||k||_2
+ * K is [B,Hkv,n,d] and S is [m,d], both of type shape->dtype.  q_heads and
+ * scale are ignored.  bf16/fp16 inputs run on the matrix cores with fp32
+ * accumulation; fp32 inputs run an fp32 FMA path.  A sign decision can differ
+ * from exact arithmetic only when |(S k)_i| is within fp32 rounding of zero
+ * (< 1e-5 * ||s_i|| * ||k||).
+ */
+int qjl_quantize_keys(const qjl_shape* shape, const void* K, const void* S,
+                      uint8_t* bits, uint16_t* norms, void* stream);
+
+/*
+ * The query side of Eq. (4): SQ[B,Hq,m] (fp32) <- S q for Q[B,Hq,d] of type
+ * shape->dtype.  The query is NOT quantized.  kv_heads, n and scale are
+ * ignored (kv_heads must still divide q_heads).
+ */
+int qjl_project_query(const qjl_shape* shape, const void* Q, const void* S,
+                      float* SQ, void* stream);
+
+/*
+ * Algorithm 1, EstimateScores before the softmax (Eq. (4) for every key):
+ *   out[B,Hq,n] (fp32) <- scale * sqrt(pi/2)/m * norms[j] * <SQ[h], sign bits of key j>
+ * SQ is [B,Hq,m] fp32 (from qjl_project_query), bits/norms as written by
+ * qjl_quantize_keys.  dtype and d are ignored.
+ */
+int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits,
+               const uint16_t* norms, float* out, void* stream);
+
+/*
+ * Bytes of device scratch qjl_decode_attention needs for this shape (query
+ * projections, per-split softmax partials, completion counters).  Returns 0
+ * for an invalid or unsupported shape.  Host only.
+ */
+size_t qjl_decode_workspace_bytes(const qjl_shape* shape);
+
+/*
+ * One decode step on a quantized key cache (Algorithm 1 EstimateScores, then
+ * Eq. (1)):  out[B,Hq,d] (fp32) <- sum_j softmax_j(scale * Prod_QJL(q_h, k_j)) * V[j,:]
+ * Q is [B,Hq,d], V is [B,Hkv,n,d], S is [m,d], all of type shape->dtype;
+ * bits/norms as written by qjl_quantize_keys.  The context is split into
+ * chunks that are processed in parallel and merged with a running
+ * max / sum-of-exponentials combine; the result does not depend on the split
+ * beyond fp32 rounding.  `workspace` is caller-owned device memory of at
+ * least qjl_decode_workspace_bytes(shape) bytes, 256-byte aligned; its
+ * contents on entry are irrelevant and undefined on exit.  Two calls that
+ * share a workspace must be ordered on the same stream.
+ */
+int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S,
+                         const uint8_t* bits, const uint16_t* norms, const void* V,
+                         float* out, void* workspace, size_t workspace_bytes,
+                         void* stream);
+
+/*
+ * qjl_decode_attention, plus kernel timing without a profiler: the two
+ * caller-owned events (hipEvent_t passed as void*, created with timing
+ * enabled; either may be NULL) are recorded on `stream` immediately before
+ * and immediately after the attention kernel (Algorithm 1 EstimateScores +
+ * Eq. (1)), i.e. after the small query-projection kernel has been enqueued.
+ * Everything else is exactly qjl_decode_attention.
+ */
+int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void* S,
+                               const uint8_t* bits, const uint16_t* norms, const void* V,
+                               float* out, void* workspace, size_t workspace_bytes,
+                               void* stream, void* event_before, void* event_after);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QJL_H_ */

@@ -1,0 +1,193 @@
+"""ctypes binding of libqjl.so: argument marshalling only.
+
+Each function has the name and meaning of the C entry point declared in
+include/qjl.h; torch is used for device memory and the current stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+QJL_F32, QJL_F16, QJL_BF16 = 0, 1, 2
+_DTYPE_TAG = {torch.float32: QJL_F32, torch.float16: QJL_F16, torch.bfloat16: QJL_BF16}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqjl.so")
+_lib: Optional[ctypes.CDLL] = None
+
+
+class QJLError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn} failed with status {status} ({text})")
+        self.status = status
+
+
+class QJLShape(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("q_heads", ctypes.c_int32), ("kv_heads", ctypes.c_int32),
+                ("n", ctypes.c_int32), ("d", ctypes.c_int32), ("m", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C library.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                           "`python -m paper_2406_03482_amd.build` (needs hipcc)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, sp = ctypes.c_void_p, ctypes.POINTER(QJLShape)
+    L.qjl_version.restype = ctypes.c_int
+    L.qjl_version.argtypes = []
+    L.qjl_status_string.restype = ctypes.c_char_p
+    L.qjl_status_string.argtypes = [ctypes.c_int]
+    L.qjl_make_sketch.restype = ctypes.c_int
+    L.qjl_make_sketch.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    L.qjl_quantize_keys.restype = ctypes.c_int
+    L.qjl_quantize_keys.argtypes = [sp, vp, vp, vp, vp, vp]
+    L.qjl_project_query.restype = ctypes.c_int
+    L.qjl_project_query.argtypes = [sp, vp, vp, vp, vp]
+    L.qjl_scores.restype = ctypes.c_int
+    L.qjl_scores.argtypes = [sp, vp, vp, vp, vp, vp]
+    L.qjl_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.qjl_decode_workspace_bytes.argtypes = [sp]
+    L.qjl_decode_attention.restype = ctypes.c_int
+    L.qjl_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_decode_attention_timed.restype = ctypes.c_int
+    L.qjl_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise QJLError(fn, status, lib().qjl_status_string(status).decode())
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _tag(t: torch.Tensor) -> int:
+    try:
+        return _DTYPE_TAG[t.dtype]
+    except KeyError:
+        raise ValueError(f"unsupported dtype {t.dtype}") from None
+
+
+def _shape(batch, q_heads, kv_heads, n, d, m, dtype_tag, scale=1.0) -> QJLShape:
+    return QJLShape(batch, q_heads, kv_heads, n, d, m, dtype_tag, scale)
+
+
+def qjl_make_sketch(seed: int, m: int, d: int, dtype: torch.dtype = torch.bfloat16,
+                    device="cuda") -> torch.Tensor:
+    """S[m,d] with i.i.d. N(0,1) entries that depend only on (seed, m, d, dtype)."""
+    S = torch.empty((m, d), dtype=dtype, device=device)
+    _check("qjl_make_sketch",
+           lib().qjl_make_sketch(seed & (2 ** 64 - 1), m, d, _tag(S), _dev(S, "S"), _stream(S)))
+    return S
+
+
+def qjl_quantize_keys(K: torch.Tensor, S: torch.Tensor, bits: Optional[torch.Tensor] = None,
+                      norms: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """K[B,Hkv,n,d], S[m,d] -> (bits uint8 [B,Hkv,n,m/8], norms float16 [B,Hkv,n])."""
+    B, Hkv, n, d = K.shape
+    m = S.shape[0]
+    if S.shape[1] != d or S.dtype != K.dtype:
+        raise ValueError("S must be [m,d] with the dtype of K")
+    if bits is None:
+        bits = torch.empty((B, Hkv, n, m // 8), dtype=torch.uint8, device=K.device)
+    if norms is None:
+        norms = torch.empty((B, Hkv, n), dtype=torch.float16, device=K.device)
+    if tuple(bits.shape) != (B, Hkv, n, m // 8) or bits.dtype != torch.uint8:
+        raise ValueError("bits must be uint8 [B,Hkv,n,m/8]")
+    if tuple(norms.shape) != (B, Hkv, n) or norms.dtype != torch.float16:
+        raise ValueError("norms must be float16 [B,Hkv,n]")
+    sh = _shape(B, Hkv, Hkv, n, d, m, _tag(K))
+    _check("qjl_quantize_keys",
+           lib().qjl_quantize_keys(ctypes.byref(sh), _dev(K, "K"), _dev(S, "S"), _dev(bits, "bits"),
+                                   _dev(norms, "norms"), _stream(K)))
+    return bits, norms
+
+
+def qjl_project_query(Q: torch.Tensor, S: torch.Tensor, SQ: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Q[B,Hq,d], S[m,d] -> SQ float32 [B,Hq,m] = S q (unquantized)."""
+    B, Hq, d = Q.shape
+    m = S.shape[0]
+    if S.shape[1] != d or S.dtype != Q.dtype:
+        raise ValueError("S must be [m,d] with the dtype of Q")
+    if SQ is None:
+        SQ = torch.empty((B, Hq, m), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, 1, 1, d, m, _tag(Q))
+    _check("qjl_project_query",
+           lib().qjl_project_query(ctypes.byref(sh), _dev(Q, "Q"), _dev(S, "S"), _dev(SQ, "SQ"),
+                                   _stream(Q)))
+    return SQ
+
+
+def qjl_scores(SQ: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor, scale: float = 1.0,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """SQ[B,Hq,m], bits[B,Hkv,n,m/8], norms[B,Hkv,n] -> float32 [B,Hq,n] (pre-softmax)."""
+    B, Hq, m = SQ.shape
+    _, Hkv, n, mb = bits.shape
+    if mb * 8 != m or SQ.dtype != torch.float32:
+        raise ValueError("SQ must be float32 [B,Hq,m] with m = 8 * bits.shape[-1]")
+    if out is None:
+        out = torch.empty((B, Hq, n), dtype=torch.float32, device=SQ.device)
+    sh = _shape(B, Hq, Hkv, n, 128, m, QJL_F32, scale)
+    _check("qjl_scores",
+           lib().qjl_scores(ctypes.byref(sh), _dev(SQ, "SQ"), _dev(bits, "bits"),
+                            _dev(norms, "norms"), _dev(out, "out"), _stream(SQ)))
+    return out
+
+
+def qjl_decode_workspace_bytes(batch: int, q_heads: int, kv_heads: int, n: int, d: int, m: int,
+                               dtype: torch.dtype = torch.bfloat16) -> int:
+    sh = _shape(batch, q_heads, kv_heads, n, d, m, _DTYPE_TAG[dtype])
+    return int(lib().qjl_decode_workspace_bytes(ctypes.byref(sh)))
+
+
+def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor,
+                         V: torch.Tensor, scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None,
+                         events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
+    """One decode step: Q[B,Hq,d], S[m,d], bits, norms, V[B,Hkv,n,d] -> float32 [B,Hq,d].
+    `events` = (hipEvent_t before, hipEvent_t after) as integers selects
+    qjl_decode_attention_timed."""
+    B, Hq, d = Q.shape
+    _, Hkv, n, _ = V.shape
+    m = S.shape[0]
+    if V.dtype != Q.dtype or S.dtype != Q.dtype:
+        raise ValueError("Q, S and V must share one dtype")
+    if tuple(bits.shape) != (B, Hkv, n, m // 8) or tuple(norms.shape) != (B, Hkv, n):
+        raise ValueError("bits/norms do not match V and S")
+    need = qjl_decode_workspace_bytes(B, Hq, Hkv, n, d, m, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, n, d, m, _tag(Q), scale)
+    args = (ctypes.byref(sh), _dev(Q, "Q"), _dev(S, "S"), _dev(bits, "bits"), _dev(norms, "norms"),
+            _dev(V, "V"), _dev(out, "out"), _dev(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream(Q))
+    if events is None:
+        _check("qjl_decode_attention", lib().qjl_decode_attention(*args))
+    else:
+        _check("qjl_decode_attention_timed", lib().qjl_decode_attention_timed(*args, events[0], events[1]))
+    return out

@@ -1,0 +1,108 @@
+// extern "C" entry points: argument validation and dispatch only.
+#include "qjl_common.hpp"
+
+using namespace qjl;
+
+namespace {
+
+bool dtype_ok(int dt) { return dt == QJL_F32 || dt == QJL_F16 || dt == QJL_BF16; }
+
+// Fields every call relies on.
+int check_shape(const qjl_shape* sh) {
+  if (!sh) return QJL_ERR_INVALID_ARG;
+  if (sh->batch < 1 || sh->q_heads < 1 || sh->kv_heads < 1 || sh->n < 1 || sh->d < 1 || sh->m < 1)
+    return QJL_ERR_INVALID_ARG;
+  if (sh->q_heads % sh->kv_heads != 0) return QJL_ERR_INVALID_ARG;
+  if (!dtype_ok(sh->dtype)) return QJL_ERR_INVALID_ARG;
+  if (!(sh->scale == sh->scale)) return QJL_ERR_INVALID_ARG;  // NaN
+  // index arithmetic inside the kernels is 64-bit, but tile counts are int
+  const long rows = (long)sh->batch * sh->kv_heads * sh->n;
+  if (rows > (1L << 40)) return QJL_ERR_UNSUPPORTED;
+  return QJL_OK;
+}
+
+bool ptr_ok(const void* p) { return p != nullptr && aligned16(p); }
+
+}  // namespace
+
+extern "C" {
+
+int qjl_version(void) { return 100; }
+
+const char* qjl_status_string(int status) {
+  switch (status) {
+    case QJL_OK: return "ok";
+    case QJL_ERR_INVALID_ARG: return "invalid argument";
+    case QJL_ERR_UNSUPPORTED: return "shape not supported by this build";
+    case QJL_ERR_WORKSPACE: return "workspace missing or too small";
+    case QJL_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int qjl_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, void* stream) {
+  if (m < 1 || d < 1 || !dtype_ok(dtype) || !ptr_ok(S)) return QJL_ERR_INVALID_ARG;
+  if ((long)m * d > (1L << 31)) return QJL_ERR_UNSUPPORTED;
+  return launch_make_sketch(seed, m, d, dtype, S, static_cast<hipStream_t>(stream));
+}
+
+int qjl_quantize_keys(const qjl_shape* shape, const void* K, const void* S, uint8_t* bits,
+                      uint16_t* norms, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(K) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms)) return QJL_ERR_INVALID_ARG;
+  if (shape->m % 32 != 0 || shape->d > 1024) return QJL_ERR_UNSUPPORTED;
+  return launch_quantize(*shape, K, S, bits, norms, static_cast<hipStream_t>(stream));
+}
+
+int qjl_project_query(const qjl_shape* shape, const void* Q, const void* S, float* SQ,
+                      void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(SQ)) return QJL_ERR_INVALID_ARG;
+  if ((long)shape->batch * shape->q_heads > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
+  return launch_project(shape->batch * shape->q_heads, shape->d, shape->m, shape->dtype, Q, S, SQ,
+                        nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
+int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits, const uint16_t* norms,
+               float* out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(SQ) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(out)) return QJL_ERR_INVALID_ARG;
+  if (shape->m != 128 && shape->m != 256 && shape->m != 512) return QJL_ERR_UNSUPPORTED;
+  return launch_scores(*shape, SQ, bits, norms, out, static_cast<hipStream_t>(stream));
+}
+
+size_t qjl_decode_workspace_bytes(const qjl_shape* shape) {
+  if (check_shape(shape) != QJL_OK) return 0;
+  decode_plan plan;
+  if (!plan_decode(*shape, &plan)) return 0;
+  return plan.total;
+}
+
+int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S, const uint8_t* bits,
+                         const uint16_t* norms, const void* V, float* out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  return qjl_decode_attention_timed(shape, Q, S, bits, norms, V, out, workspace, workspace_bytes,
+                                    stream, nullptr, nullptr);
+}
+
+int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void* S,
+                               const uint8_t* bits, const uint16_t* norms, const void* V,
+                               float* out, void* workspace, size_t workspace_bytes, void* stream,
+                               void* event_before, void* event_after) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(V) || !ptr_ok(out))
+    return QJL_ERR_INVALID_ARG;
+  decode_plan plan;
+  if (!plan_decode(*shape, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  return launch_decode(*shape, plan, Q, S, bits, norms, V, out, workspace,
+                       static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
+                       static_cast<hipEvent_t>(event_after));
+}
+
+}  // extern "C"

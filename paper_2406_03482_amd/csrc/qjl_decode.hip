@@ -1,0 +1,411 @@
+// One decode step on a quantized key cache: Algorithm 1 EstimateScores
+// (Definition 3.1 Eq. (4) for every key, then softmax) followed by the value
+// aggregation of Section 2 Eq. (1), fused in one streaming pass.
+//
+// HBM-bound: per key and KV head the kernel reads m/8 code bytes, a 2-byte
+// norm and one row of V, nothing else of size.  The context is cut into
+// chunks (one workgroup each); every wave keeps a running (max, sum, o[d])
+// and the partial results are merged wave -> workgroup -> last workgroup of
+// the unit with the usual max/sum-of-exponentials rescaling.
+#include "qjl_common.hpp"
+#include "qjl_lut.hpp"
+
+#include <stdlib.h>
+
+namespace qjl {
+namespace {
+
+constexpr int kD = 128;          // head dimension this kernel is written for
+constexpr int kPartStride = 132; // floats per partial record: max, sum, 2 pad, o[128]
+
+// LDS bytes of one workgroup: S q (gt*m floats), 4-bit tables (4*gt*m), byte
+// tables (32*gt*m).  Everything else aliases onto tables that are dead by then.
+constexpr size_t decode_lds_bytes(int gt, int m) { return (size_t)gt * m * 37 * sizeof(float); }
+
+// Waves per workgroup: small tables let four workgroups share the 160 KiB of a
+// CU (four waves each); larger tables mean one or two workgroups per CU, which
+// then get eight waves so that every SIMD still has two to switch between.
+constexpr int decode_waves(int gt, int m) { return decode_lds_bytes(gt, m) <= 40 * 1024 ? 4 : 8; }
+
+struct decode_args {
+  const float* SQ;        // [B,Hq,m]
+  const uint8_t* bits;    // [B,Hkv,n,m/8]
+  const uint16_t* norms;  // [B,Hkv,n]
+  const void* V;          // [B,Hkv,n,128]
+  float* part;            // [B,Hq,nsplit,132]
+  uint32_t* cnt;          // [units]
+  float* out;             // [B,Hq,128]
+  int n, q_heads, kv_heads, groups_per_kv;
+  int nsplit, chunk;
+  float coef2;            // scale * sqrt(pi/2) / m * log2(e)
+};
+
+// 16 bytes of V -> 8 floats (16-bit types) ...
+template <typename T> struct vtile {
+  static constexpr int kRegs = 1;  // uint4 per 8 elements
+  uint4 r;
+  __device__ __forceinline__ void load(const void* V, size_t elem) {
+    r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(V) + elem);
+  }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    unpack2<T>(r.x, x[0], x[1]); unpack2<T>(r.y, x[2], x[3]);
+    unpack2<T>(r.z, x[4], x[5]); unpack2<T>(r.w, x[6], x[7]);
+  }
+};
+// ... or 32 bytes (fp32).
+template <> struct vtile<f32_t> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const void* V, size_t elem) {
+    const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(V) + elem);
+    a = p[0]; b = p[1];
+  }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+};
+
+template <typename T, int GT, int MW>
+__global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(decode_args a) {
+  constexpr int kNW = decode_waves(GT, MW * 32);
+  extern __shared__ float4 smem4[];
+  float* smem = reinterpret_cast<float*>(smem4);
+  constexpr int M = MW * 32;
+  float* sq = smem;
+  float* nib = sq + GT * M;
+  float* lut = nib + 4 * M * GT;
+  // the 4-bit tables are dead once the byte tables exist; their space then
+  // holds the per-wave probability buffers.  The wave-merge records reuse the
+  // byte tables after the last key has been scored.
+  float* pbuf_all = nib;                              // [kNW][64*GT]
+  float* merge = lut;                                 // [kNW][GT][132]
+  static_assert(kNW * 64 <= 4 * M, "probability buffers must fit the 4-bit tables");
+  static_assert(kNW * kPartStride <= 32 * M, "merge records must fit the byte tables");
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int unit = blockIdx.x / a.nsplit;
+  const int split = blockIdx.x - unit * a.nsplit;
+  const int gg = unit % a.groups_per_kv;
+  const int bk = unit / a.groups_per_kv;              // b * Hkv + kvh
+  const int b = bk / a.kv_heads, kvh = bk - b * a.kv_heads;
+  const int G = a.groups_per_kv * GT;
+  const size_t hq0 = (size_t)b * a.q_heads + (size_t)kvh * G + (size_t)gg * GT;
+
+  for (int e = tid; e < GT * M; e += kNW * 64) sq[e] = a.SQ[hq0 * M + e];
+  __syncthreads();
+  build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
+  // build_lut ends with a barrier: nobody reads `nib` any more.
+
+  const int k_begin = split * a.chunk;
+  const int k_end = min(a.n, k_begin + a.chunk);
+  const size_t row0 = (size_t)bk * a.n;
+  float* pbuf = pbuf_all + wave * 64 * GT;
+  const int r = lane >> 4;                            // row of a 4-row V pass
+  const int c = lane & 15;                            // 8-channel slice
+
+  float m_run[GT], l_lane[GT], acc[GT][8];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    m_run[g] = -INFINITY;
+    l_lane[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+
+  int k0 = k_begin + wave * 64;
+  uint32_t wcur[MW];
+  float ncur = 0.f;
+  if (k0 < k_end) {
+    const int j = min(k0 + lane, k_end - 1);
+    load_code<MW>(a.bits, row0 + j, wcur);
+    ncur = f16_bits_to_float(a.norms[row0 + j]);
+  }
+
+  for (; k0 < k_end; k0 += kNW * 64) {
+    // ---- issue this block's V loads (rows past the chunk end are clamped; their weight is 0).
+    // 16-bit values: all 16 row passes are in flight while the scores are computed;
+    // fp32 values take twice the registers, so their second half is loaded later.
+    constexpr int IB = T::bytes == 2 ? 16 : 8;
+    vtile<T> v[IB];
+#pragma unroll
+    for (int i = 0; i < IB; ++i) {
+      const int j = min(k0 + 4 * i + r, k_end - 1);
+      v[i].load(a.V, (row0 + j) * kD + c * 8);
+    }
+    // ---- prefetch the next block's codes and norms
+    const int kn = k0 + kNW * 64;
+    uint32_t wnext[MW];
+    float nnext = 0.f;
+    if (kn < k_end) {
+      const int j = min(kn + lane, k_end - 1);
+      load_code<MW>(a.bits, row0 + j, wnext);
+      nnext = f16_bits_to_float(a.norms[row0 + j]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < MW; ++i) wnext[i] = 0u;
+    }
+    // ---- scores of this block: lane <-> key
+    float s[GT];
+    key_inner<GT, MW>(wcur, lut, s);
+    const bool valid = (k0 + lane) < k_end;
+    float alpha[GT], p[GT];
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const float sg = valid ? s[g] * ncur * a.coef2 : -INFINITY;   // log2 domain
+      const float m_new = fmaxf(m_run[g], wave_max(sg));
+      alpha[g] = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+      p[g] = __builtin_amdgcn_exp2f(sg - m_new);
+      l_lane[g] = l_lane[g] * alpha[g] + p[g];
+      m_run[g] = m_new;
+    }
+    // key (4i + r) of the block goes to slot r*16 + i, so that a V lane reads
+    // its 16 weights from consecutive slots
+    {
+      const int slot = (lane & 3) * 16 + (lane >> 2);
+      using PV = typename vecf<GT>::type;
+      PV pv;
+      if constexpr (GT == 1) pv = p[0];
+      else if constexpr (GT == 2) pv = make_float2(p[0], p[1]);
+      else pv = make_float4(p[0], p[1], p[2], p[3]);
+      reinterpret_cast<PV*>(pbuf)[slot] = pv;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- o = o * alpha + sum_j p_j v_j
+#pragma unroll
+    for (int g = 0; g < GT; ++g)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] *= alpha[g];
+#pragma unroll
+    for (int i0 = 0; i0 < 16; i0 += IB) {
+      if (i0 > 0) {
+#pragma unroll
+        for (int i = 0; i < IB; ++i) {
+          const int j = min(k0 + 4 * (i0 + i) + r, k_end - 1);
+          v[i].load(a.V, (row0 + j) * kD + c * 8);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < IB; ++i) {
+        float x[8];
+        v[i].get(x);
+        using PV = typename vecf<GT>::type;
+        const PV pv = reinterpret_cast<const PV*>(pbuf)[r * 16 + i0 + i];
+        float pg[GT];
+        if constexpr (GT == 1) { pg[0] = pv; }
+        else if constexpr (GT == 2) { pg[0] = pv.x; pg[1] = pv.y; }
+        else { pg[0] = pv.x; pg[1] = pv.y; pg[2] = pv.z; pg[3] = pv.w; }
+#pragma unroll
+        for (int g = 0; g < GT; ++g)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pg[g], x[e], acc[g][e]);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int i = 0; i < MW; ++i) wcur[i] = wnext[i];
+    ncur = nnext;
+  }
+
+  __syncthreads();   // every wave is done with the tables: their space now takes the merge records
+  // ---- wave result: sum over lanes / over the four row groups
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    const float l = wave_sum(l_lane[g]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x = acc[g][e];
+      x += __shfl_xor(x, 16);
+      x += __shfl_xor(x, 32);
+      acc[g][e] = x;
+    }
+    float* rec = merge + (wave * GT + g) * kPartStride;
+    if (lane < 16) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = acc[g][e];
+    }
+    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l; }
+  }
+  __syncthreads();
+
+  // ---- workgroup result: merge the waves
+  for (int idx = tid; idx < GT * kD; idx += kNW * 64) {
+    const int g = idx >> 7, ch = idx & 127;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kNW; ++w) mx = fmaxf(mx, merge[(w * GT + g) * kPartStride]);
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < kNW; ++w) {
+      const float* rec = merge + (w * GT + g) * kPartStride;
+      const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
+      L = fmaf(rec[1], f, L);
+      O = fmaf(rec[4 + ch], f, O);
+    }
+    if (a.nsplit == 1) {
+      a.out[(hq0 + g) * kD + ch] = O / L;
+    } else {
+      float* rec = a.part + ((hq0 + g) * a.nsplit + split) * kPartStride;
+      rec[4 + ch] = O;
+      if (ch == 0) { rec[0] = mx; rec[1] = L; }
+    }
+  }
+  if (a.nsplit == 1) return;
+
+  // ---- the workgroup that finishes last for this unit merges the chunks
+  __shared__ int s_last;
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) s_last = (atomicAdd(&a.cnt[unit], 1u) == (uint32_t)(a.nsplit - 1)) ? 1 : 0;
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int idx = tid; idx < GT * kD; idx += kNW * 64) {
+    const int g = idx >> 7, ch = idx & 127;
+    const float* base = a.part + (hq0 + g) * (size_t)a.nsplit * kPartStride;
+    float mx = -INFINITY;
+    for (int s2 = 0; s2 < a.nsplit; ++s2) mx = fmaxf(mx, base[(size_t)s2 * kPartStride]);
+    float L = 0.f, O = 0.f;
+    for (int s2 = 0; s2 < a.nsplit; ++s2) {
+      const float* rec = base + (size_t)s2 * kPartStride;
+      const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
+      L = fmaf(rec[1], f, L);
+      O = fmaf(rec[4 + ch], f, O);
+    }
+    a.out[(hq0 + g) * kD + ch] = O / L;
+  }
+}
+
+template <typename T, int GT, int MW>
+int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st) {
+  static bool attr_set = false;
+  constexpr int kNW = decode_waves(GT, MW * 32);
+  const size_t lds = decode_lds_bytes(GT, MW * 32);
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_status(e);
+    attr_set = true;
+  }
+  const long units = (long)sh.batch * sh.kv_heads * a.groups_per_kv;
+  const long total = units * plan.nsplit;
+  if (total > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64), lds, st, a);
+  return launch_status();
+}
+
+template <typename T, int MW>
+int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st) {
+  switch (plan.gt) {
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW>(sh, plan, a, st); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW>(sh, plan, a, st); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW>(sh, plan, a, st);
+  }
+}
+
+template <typename T>
+int launch_m(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st) {
+  switch (sh.m) {
+    case 128: return launch_g<T, 4>(sh, plan, a, st);
+    case 256: return launch_g<T, 8>(sh, plan, a, st);
+    case 512: return launch_g<T, 16>(sh, plan, a, st);
+    default: return QJL_ERR_UNSUPPORTED;
+  }
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+int device_cu_count() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+    cached = cus;
+    return cus;
+  }
+  (void)hipGetLastError();
+  return 256;  // MI355X; used when no device is visible (host-only callers)
+}
+
+// How the context is cut up.  One "unit" is a (batch, kv head, group of GT
+// query heads); it gets nsplit workgroups of `chunk` keys each.
+bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
+  if (sh.d != kD) return false;
+  if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
+  const int G = sh.q_heads / sh.kv_heads;
+  int gt = 1;
+  if (G % 4 == 0 && sh.m * 4 <= 1024) gt = 4;
+  else if (G % 2 == 0 && sh.m * 2 <= 1024) gt = 2;
+  const long units = (long)sh.batch * sh.kv_heads * (G / gt);
+  const size_t lds = decode_lds_bytes(gt, sh.m);
+  long occ = (160 * 1024) / (long)lds;              // workgroups per CU by LDS
+  if (occ < 1) occ = 1;
+  if (occ > 4) occ = 4;
+  const long slots = (long)device_cu_count() * occ;
+  long nsplit = (slots + units - 1) / units;
+  const long min_chunk = 64L * decode_waves(gt, sh.m);  // one 64-key block per wave
+  long max_split = ((long)sh.n + min_chunk - 1) / min_chunk;
+  if (nsplit > max_split) nsplit = max_split;
+  if (nsplit > 512) nsplit = 512;
+  if (const char* e = getenv("QJL_DECODE_SPLITS")) {  // tuning knob for experiments
+    long v = atol(e);
+    if (v >= 1 && v <= 4096) nsplit = v;
+  }
+  if (nsplit < 1) nsplit = 1;
+  long chunk = ((long)sh.n + nsplit - 1) / nsplit;
+  chunk = (chunk + 63) / 64 * 64;
+  nsplit = ((long)sh.n + chunk - 1) / chunk;
+  plan->gt = gt;
+  plan->nsplit = (int)nsplit;
+  plan->chunk = (int)chunk;
+  size_t off = 0;
+  plan->off_sq = off;
+  off = align_up(off + (size_t)sh.batch * sh.q_heads * sh.m * sizeof(float), 256);
+  plan->off_part = off;
+  off = align_up(off + (size_t)sh.batch * sh.q_heads * nsplit * kPartStride * sizeof(float), 256);
+  plan->off_cnt = off;
+  plan->n_cnt = (size_t)units;
+  off = align_up(off + (size_t)units * sizeof(uint32_t), 256);
+  plan->total = off;
+  return true;
+}
+
+int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, const void* S,
+                  const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
+                  void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
+  char* ws = static_cast<char*>(workspace);
+  float* SQ = reinterpret_cast<float*>(ws + plan.off_sq);
+  uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + plan.off_cnt);
+  // kernel 1: S q for every query head, and clear the completion counters
+  int rc = launch_project(sh.batch * sh.q_heads, sh.d, sh.m, sh.dtype, Q, S, SQ, cnt,
+                          (int)plan.n_cnt, st);
+  if (rc != QJL_OK) return rc;
+  decode_args a;
+  a.SQ = SQ; a.bits = bits; a.norms = norms; a.V = V;
+  a.part = reinterpret_cast<float*>(ws + plan.off_part);
+  a.cnt = cnt; a.out = out;
+  a.n = sh.n; a.q_heads = sh.q_heads; a.kv_heads = sh.kv_heads;
+  a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
+  a.nsplit = plan.nsplit; a.chunk = plan.chunk;
+  a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
+  if (ev_before) {
+    hipError_t e = hipEventRecord(ev_before, st);
+    if (e != hipSuccess) return hip_status(e);
+  }
+  switch (sh.dtype) {
+    case QJL_F32: rc = launch_m<f32_t>(sh, plan, a, st); break;
+    case QJL_F16: rc = launch_m<f16_t>(sh, plan, a, st); break;
+    default: rc = launch_m<bf16_t>(sh, plan, a, st); break;
+  }
+  if (rc == QJL_OK && ev_after) rc = hip_status(hipEventRecord(ev_after, st));
+  return rc;
+}
+
+}  // namespace qjl

@@ -1,0 +1,100 @@
+// Byte-indexed partial-sum tables for <S q, sign bits> (Definition 3.1 Eq. (4)).
+//
+// For byte position p of a key's code and byte value b,
+//     T[p][b] = sum_{t<8} (bit t of b ? +1 : -1) * (S q)[8p + t],
+// so the inner product with one key is the sum of m/8 table entries selected
+// by the key's code bytes.  Tables for GT query heads that share a KV head are
+// interleaved (GT consecutive floats per entry) so one LDS read serves all.
+// The tables are built in two stages from 4-bit tables so that each entry
+// costs one add.
+#pragma once
+
+#include "qjl_common.hpp"
+
+namespace qjl {
+
+template <int GT> struct vecf;
+template <> struct vecf<1> { using type = float; };
+template <> struct vecf<2> { using type = float2; };
+template <> struct vecf<4> { using type = float4; };
+
+// LDS floats needed: sq GT*m, 4-bit tables 4*m*GT, byte tables 32*m*GT.
+template <int GT> __host__ __device__ constexpr size_t lut_lds_floats(int m) {
+  return (size_t)GT * m * (1 + 4 + 32);
+}
+
+// sq: [GT][m] in LDS (already filled, visible to all threads).
+// nib: [(m/4)][16][GT], lut: [(m/8)][256][GT].  Ends with a barrier.
+template <int GT>
+__device__ __forceinline__ void build_lut(const float* sq, float* nib, float* lut, int m, int tid,
+                                          int nthreads) {
+  const int n_nib = (m >> 2) << 4;
+  for (int e = tid; e < n_nib; e += nthreads) {
+    const int q = e >> 4, x = e & 15;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const float* s = sq + g * m + 4 * q;
+      float v0 = (x & 1) ? s[0] : -s[0];
+      float v1 = (x & 2) ? s[1] : -s[1];
+      float v2 = (x & 4) ? s[2] : -s[2];
+      float v3 = (x & 8) ? s[3] : -s[3];
+      nib[e * GT + g] = (v0 + v1) + (v2 + v3);
+    }
+  }
+  __syncthreads();
+  using V = typename vecf<GT>::type;
+  const V* nibv = reinterpret_cast<const V*>(nib);
+  V* lutv = reinterpret_cast<V*>(lut);
+  const int n_byte = (m >> 3) << 8;
+  for (int e = tid; e < n_byte; e += nthreads) {
+    const int p = e >> 8, b = e & 255;
+    V lo = nibv[(2 * p) * 16 + (b & 15)];
+    V hi = nibv[(2 * p + 1) * 16 + (b >> 4)];
+    V r;
+    if constexpr (GT == 1) { r = lo + hi; }
+    else if constexpr (GT == 2) { r = make_float2(lo.x + hi.x, lo.y + hi.y); }
+    else { r = make_float4(lo.x + hi.x, lo.y + hi.y, lo.z + hi.z, lo.w + hi.w); }
+    lutv[e] = r;
+  }
+  __syncthreads();
+}
+
+// <S q_g, signs of one key> for g < GT, from the key's MW code words.
+template <int GT, int MW>
+__device__ __forceinline__ void key_inner(const uint32_t (&w)[MW], const float* lut,
+                                          float (&out)[GT]) {
+  using V = typename vecf<GT>::type;
+  const V* lutv = reinterpret_cast<const V*>(lut);
+  float a0[GT], a1[GT];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) { a0[g] = 0.f; a1[g] = 0.f; }
+#pragma unroll
+  for (int wi = 0; wi < MW; ++wi) {
+#pragma unroll
+    for (int by = 0; by < 4; ++by) {
+      const int p = wi * 4 + by;
+      const uint32_t b = (w[wi] >> (8 * by)) & 255u;
+      V e = lutv[p * 256 + b];
+      float* a = (by & 1) ? a1 : a0;
+      if constexpr (GT == 1) { a[0] += e; }
+      else if constexpr (GT == 2) { a[0] += e.x; a[1] += e.y; }
+      else { a[0] += e.x; a[1] += e.y; a[2] += e.z; a[3] += e.w; }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < GT; ++g) out[g] = a0[g] + a1[g];
+}
+
+// Load the MW code words of one key (row `row` of bits[*, MW*4 bytes]).
+template <int MW>
+__device__ __forceinline__ void load_code(const uint8_t* __restrict__ bits, size_t row,
+                                          uint32_t (&w)[MW]) {
+  const uint4* p = reinterpret_cast<const uint4*>(bits + row * (size_t)(MW * 4));
+#pragma unroll
+  for (int i = 0; i < MW / 4; ++i) {
+    uint4 r = p[i];
+    w[4 * i + 0] = r.x; w[4 * i + 1] = r.y; w[4 * i + 2] = r.z; w[4 * i + 3] = r.w;
+  }
+}
+
+}  // namespace qjl

@@ -1,0 +1,76 @@
+// The query side of Definition 3.1 Eq. (4): SQ = S q, with the query left
+// unquantized.  fp32 accumulation.  One workgroup per query vector.
+#include "qjl_common.hpp"
+
+namespace qjl {
+namespace {
+
+// d == 128: sixteen lanes share one row of S (16 bytes each, so a wave reads
+// four whole rows per load), multiply by their slice of q held in registers
+// and reduce inside the 16-lane DPP row.
+template <typename T>
+__global__ void __launch_bounds__(256)
+project128_kernel(const void* __restrict__ Q, const void* __restrict__ S, float* __restrict__ SQ,
+                  int m, uint32_t* __restrict__ zero_words, int n_zero_words) {
+  const int row = blockIdx.x;                 // (b, hq) flattened
+  const int tid = threadIdx.x;
+  // the first workgroups also clear the caller's completion counters
+  for (int i = row * 256 + tid; i < n_zero_words; i += gridDim.x * 256) zero_words[i] = 0u;
+
+  const int c = tid & 15;                     // 8-element slice of the row
+  const int r = tid >> 4;                     // 0..15: row inside a pass of 16 rows
+  float q[8];
+  load8<T>(Q, (size_t)row * 128 + c * 8, q);
+  for (int i0 = 0; i0 < m; i0 += 16) {
+    int i = i0 + r;
+    int ic = i < m ? i : m - 1;               // clamp: never read past S
+    float s[8];
+    load8<T>(S, (size_t)ic * 128 + c * 8, s);
+    float acc = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc = fmaf(s[t], q[t], acc);
+    acc = row16_sum(acc);
+    if (c == 0 && i < m) SQ[(size_t)row * m + i] = acc;
+  }
+}
+
+// Any d, any m: one thread per projection, scalar loads.
+template <typename T>
+__global__ void __launch_bounds__(256)
+project_generic_kernel(const void* __restrict__ Q, const void* __restrict__ S,
+                       float* __restrict__ SQ, int d, int m, uint32_t* __restrict__ zero_words,
+                       int n_zero_words) {
+  const int row = blockIdx.x;
+  const int tid = threadIdx.x;
+  for (int i = row * 256 + tid; i < n_zero_words; i += gridDim.x * 256) zero_words[i] = 0u;
+  for (int i = tid; i < m; i += 256) {
+    float acc = 0.f;
+    for (int t = 0; t < d; ++t)
+      acc = fmaf(load1<T>(S, (size_t)i * d + t), load1<T>(Q, (size_t)row * d + t), acc);
+    SQ[(size_t)row * m + i] = acc;
+  }
+}
+
+template <typename T>
+int launch_t(int rows, int d, int m, const void* Q, const void* S, float* SQ, uint32_t* zw, int nzw,
+             hipStream_t st) {
+  dim3 grid((unsigned)rows), block(256);
+  if (d == 128)
+    hipLaunchKernelGGL(project128_kernel<T>, grid, block, 0, st, Q, S, SQ, m, zw, nzw);
+  else
+    hipLaunchKernelGGL(project_generic_kernel<T>, grid, block, 0, st, Q, S, SQ, d, m, zw, nzw);
+  return launch_status();
+}
+
+}  // namespace
+
+int launch_project(int rows, int d, int m, int dtype, const void* Q, const void* S, float* SQ,
+                   uint32_t* zero_words, int n_zero_words, hipStream_t st) {
+  switch (dtype) {
+    case QJL_F32: return launch_t<f32_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
+    case QJL_F16: return launch_t<f16_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
+    default: return launch_t<bf16_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
+  }
+}
+
+}  // namespace qjl

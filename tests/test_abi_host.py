@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/qjl.h declares, and rejects bad arguments on the host
+before anything is launched (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2406_03482_amd as qjl
+from paper_2406_03482_amd import QJLShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE, HIP = 0, -1, -2, -3, -4
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(qjl.lib_path()):
+        from paper_2406_03482_amd import build
+        build.build(verbose=False)
+    return qjl.lib()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qjl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qjl_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    names = _declared_symbols()
+    assert names == ["qjl_decode_attention", "qjl_decode_attention_timed",
+                     "qjl_decode_workspace_bytes", "qjl_make_sketch",
+                     "qjl_project_query", "qjl_quantize_keys", "qjl_scores", "qjl_status_string",
+                     "qjl_version"]
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(L):
+    assert L.qjl_version() >= 100
+    texts = {s: L.qjl_status_string(s).decode() for s in (OK, INVALID, UNSUPPORTED, WORKSPACE, HIP, -99)}
+    assert texts[OK] == "ok" and len(set(texts.values())) == 6
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(QJLShape) == 32
+    assert [f[0] for f in QJLShape._fields_] == ["batch", "q_heads", "kv_heads", "n", "d", "m",
+                                                 "dtype", "scale"]
+
+
+GOOD = dict(batch=1, q_heads=32, kv_heads=8, n=4096, d=128, m=256, dtype=2, scale=1.0)
+PTR = 0x1000  # never dereferenced: every call below must fail validation first
+
+
+def _sh(**kw):
+    a = dict(GOOD)
+    a.update(kw)
+    return QJLShape(a["batch"], a["q_heads"], a["kv_heads"], a["n"], a["d"], a["m"], a["dtype"], a["scale"])
+
+
+def test_null_and_misaligned_pointers_are_rejected(L):
+    sh = _sh()
+    assert L.qjl_make_sketch(1, 256, 128, 2, None, None) == INVALID
+    assert L.qjl_make_sketch(1, 256, 128, 2, PTR + 2, None) == INVALID
+    assert L.qjl_make_sketch(1, 0, 128, 2, PTR, None) == INVALID
+    assert L.qjl_make_sketch(1, 256, 128, 7, PTR, None) == INVALID
+    assert L.qjl_quantize_keys(None, PTR, PTR, PTR, PTR, None) == INVALID
+    for bad in range(4):
+        args = [PTR] * 4
+        args[bad] = None
+        assert L.qjl_quantize_keys(ctypes.byref(sh), *args, None) == INVALID
+        args[bad] = PTR + 4
+        assert L.qjl_quantize_keys(ctypes.byref(sh), *args, None) == INVALID
+    for bad in range(3):
+        args = [PTR] * 3
+        args[bad] = None
+        assert L.qjl_project_query(ctypes.byref(sh), *args, None) == INVALID
+    for bad in range(4):
+        args = [PTR] * 4
+        args[bad] = None
+        assert L.qjl_scores(ctypes.byref(sh), *args, None) == INVALID
+    for bad in range(6):
+        args = [PTR] * 6
+        args[bad] = None
+        assert L.qjl_decode_attention(ctypes.byref(sh), *args, PTR, 1 << 30, None) == INVALID
+
+
+@pytest.mark.parametrize("field,value", [("batch", 0), ("q_heads", 0), ("kv_heads", 0), ("n", 0),
+                                         ("n", -5), ("d", 0), ("m", 0), ("dtype", 3), ("dtype", -1),
+                                         ("kv_heads", 5), ("scale", float("nan"))])
+def test_invalid_shapes_are_rejected(L, field, value):
+    sh = _sh(**{field: value})
+    assert L.qjl_quantize_keys(ctypes.byref(sh), PTR, PTR, PTR, PTR, None) == INVALID
+    assert L.qjl_project_query(ctypes.byref(sh), PTR, PTR, PTR, None) == INVALID
+    assert L.qjl_scores(ctypes.byref(sh), PTR, PTR, PTR, PTR, None) == INVALID
+    assert L.qjl_decode_attention(ctypes.byref(sh), PTR, PTR, PTR, PTR, PTR, PTR, PTR, 1 << 30, None) == INVALID
+    assert L.qjl_decode_workspace_bytes(ctypes.byref(sh)) == 0
+
+
+def test_unsupported_shapes_are_reported_as_such(L):
+    assert L.qjl_quantize_keys(ctypes.byref(_sh(m=100)), PTR, PTR, PTR, PTR, None) == UNSUPPORTED
+    assert L.qjl_quantize_keys(ctypes.byref(_sh(d=4096)), PTR, PTR, PTR, PTR, None) == UNSUPPORTED
+    assert L.qjl_scores(ctypes.byref(_sh(m=96)), PTR, PTR, PTR, PTR, None) == UNSUPPORTED
+    for kw in (dict(d=64), dict(m=96), dict(m=1024)):
+        sh = _sh(**kw)
+        assert L.qjl_decode_workspace_bytes(ctypes.byref(sh)) == 0
+        assert L.qjl_decode_attention(ctypes.byref(sh), PTR, PTR, PTR, PTR, PTR, PTR, PTR, 1 << 30,
+                                      None) == UNSUPPORTED
+
+
+def test_workspace_contract(L):
+    sh = _sh()
+    need = L.qjl_decode_workspace_bytes(ctypes.byref(sh))
+    assert need > 0 and need % 256 == 0
+    # room for S q alone is a lower bound
+    assert need >= GOOD["batch"] * GOOD["q_heads"] * GOOD["m"] * 4
+    call = lambda ws, nbytes: L.qjl_decode_attention(ctypes.byref(sh), PTR, PTR, PTR, PTR, PTR, PTR,
+                                                     ws, nbytes, None)
+    assert call(None, need) == WORKSPACE
+    assert call(0x10000, need - 1) == WORKSPACE
+    assert call(0x10000 + 16, need) == INVALID          # workspace must be 256-byte aligned
+    # grows with the problem, never shrinks below the S q area
+    big = L.qjl_decode_workspace_bytes(ctypes.byref(_sh(batch=16)))
+    assert big > need
+
+
+def test_python_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        qjl.qjl_project_query(torch.zeros(1, 1, 128), torch.zeros(256, 128))

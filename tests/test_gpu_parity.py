@@ -1,0 +1,376 @@
+"""GPU-vs-oracle parity, through the C ABI (python binding = marshalling only).
+
+Tolerances (stated by the build's goal):
+  * packed sign bits: bit-exact, except entries with |(S k)_i| < 1e-5 ||s_i|| ||k||,
+    which are counted and reported;
+  * norms and scores: 1e-3 relative (scores: relative to max(|ref|, 1e-2 rms of
+    the head's scores), since an unbiased estimate of a small inner product can
+    be arbitrarily close to zero);
+  * attention outputs: 2e-3 max absolute error.
+Each stage is fed the oracle's own outputs of the stage before it, so that no
+oracle input comes from the GPU.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_03482_amd as qjl
+from paper_2406_03482_amd import inputs
+from oracle import qjl_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+DT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    assert os.path.exists(qjl.lib_path()), "libqjl.so must be built before the GPU tests run"
+    qjl.lib()
+
+
+# ------------------------------------------------------------------ comparison helpers
+def bits_report(bits_gpu: np.ndarray, K64: np.ndarray, S64: np.ndarray):
+    """(mismatches outside the near-zero band, flips inside it, entries inside it)."""
+    ref_bits, _, P = orc.quantize_keys(K64, S64)
+    m = S64.shape[0]
+    diff = orc.unpack_signs(bits_gpu, m) != orc.unpack_signs(ref_bits, m)
+    band = np.abs(P) < 1e-5 * np.linalg.norm(S64, axis=1) * np.linalg.norm(K64, axis=-1, keepdims=True)
+    return int((diff & ~band).sum()), int((diff & band).sum()), int(band.sum())
+
+
+def assert_norms(norms_gpu: np.ndarray, K64: np.ndarray):
+    ref = np.linalg.norm(K64, axis=-1)
+    got = norms_gpu.astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 1e-3 * ref + 1e-30)
+    # and never further than one binary16 step from the oracle's stored value
+    ref16 = orc.key_norms(K64)
+    step = np.abs(np.nextafter(ref16, np.float16(np.inf)).astype(np.float64) - ref16.astype(np.float64))
+    assert np.all(np.abs(got - ref16.astype(np.float64)) <= step)
+    return float(np.mean(norms_gpu == ref16))
+
+
+def assert_scores(got: np.ndarray, ref: np.ndarray):
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    tol = 1e-3 * np.maximum(np.abs(ref), 1e-2 * rms)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.all(err <= tol), f"score error {float((err / tol).max()):.3g} x tolerance"
+    return float((err / tol).max())
+
+
+def assert_attention(got: np.ndarray, ref: np.ndarray):
+    err = float(np.max(np.abs(got.astype(np.float64) - ref)))
+    assert err <= 2e-3, f"attention max abs error {err:.3g}"
+    return err
+
+
+def oracle_cache(K, S):
+    """Oracle-quantized cache of K, uploaded: (bits, norms) device tensors + numpy twins."""
+    bits, nu16, _ = orc.quantize_keys(inputs.to_f64(K), inputs.to_f64(S))
+    return (torch.from_numpy(bits).to(DEV), torch.from_numpy(nu16).to(DEV)), (bits, nu16)
+
+
+# ------------------------------------------------------------------ a0: the sketch
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("m,d,seed", [(256, 128, 1), (512, 128, 4), (40, 24, 99)])
+def test_make_sketch_matches_oracle_generator(dt, m, d, seed):
+    say(f"[sketch] dt={dt} m={m} d={d} seed={seed}")
+    S = qjl.qjl_make_sketch(seed, m, d, DT[dt], DEV)
+    got = inputs.to_f64(S)
+    ref = orc.gaussian_sketch(seed, m, d, dt)
+    exact = float(np.mean(got == ref))
+    ulp = {"f32": 2.0 ** -23, "bf16": 2.0 ** -7, "f16": 2.0 ** -10}[dt]
+    assert np.all(np.abs(got - ref) <= ulp * np.maximum(np.abs(ref), 2.0 ** -14))
+    assert exact > 0.999                      # libm differences may move a rounding, rarely
+    S2 = qjl.qjl_make_sketch(seed, m, d, DT[dt], DEV)
+    assert torch.equal(S, S2)
+    say(f"  exact fraction {exact:.6f}")
+
+
+# ------------------------------------------------------------------ a1-a3: quantize keys
+QUANT_CASES = [
+    # dt, B, Hkv, n, d, m, outliers
+    ("bf16", 1, 2, 1000, 128, 256, 4),       # MFMA, ragged last tile
+    ("bf16", 2, 3, 257, 128, 512, 4),        # MFMA m=512 (128 projections per wave)
+    ("bf16", 1, 1, 95, 128, 128, 4),         # MFMA m=128 (32 projections per wave, 16-bit stores)
+    ("bf16", 1, 1, 70, 128, 384, 0),         # three blocks of 128 projections
+    ("bf16", 1, 1, 33, 128, 1024, 0),        # two blocks of 512 projections
+    ("f16", 1, 2, 513, 128, 256, 4),         # fp16 MFMA
+    ("f16", 1, 1, 64, 128, 512, 0),
+    ("bf16", 1, 1, 1, 128, 256, 0),          # a single key
+    ("bf16", 1, 1, 31, 128, 256, 4),         # fewer keys than one tile
+    ("f32", 1, 1, 1024, 128, 256, 0),        # config 1 keys: fp32 FMA path
+    ("f32", 2, 2, 37, 128, 512, 4),
+    ("bf16", 1, 2, 50, 64, 96, 0),           # generic path: other d, m % 32 == 0
+    ("f16", 1, 1, 19, 40, 32, 0),
+    ("f32", 1, 1, 9, 8, 32, 0),
+]
+
+
+@pytest.mark.parametrize("dt,B,Hkv,n,d,m,outl", QUANT_CASES)
+def test_quantize_keys_parity(dt, B, Hkv, n, d, m, outl):
+    say(f"[quantize] dt={dt} B={B} Hkv={Hkv} n={n} d={d} m={m}")
+    K = inputs.make_keys(B, Hkv, n, d, DT[dt], 7 + n, DEV, outliers=outl)
+    S = qjl.qjl_make_sketch(3, m, d, DT[dt], DEV)
+    bits, norms = qjl.qjl_quantize_keys(K, S)
+    torch.cuda.synchronize()
+    K64, S64 = inputs.to_f64(K), inputs.to_f64(S)
+    bad, flips, inband = bits_report(bits.cpu().numpy(), K64, S64)
+    say(f"  bits: {bad} mismatches outside the band, {flips} flips among {inband} near-zero entries "
+        f"of {B * Hkv * n * m}")
+    assert bad == 0
+    same = assert_norms(norms.cpu().numpy(), K64)
+    say(f"  norms: {same:.4f} identical to the oracle's binary16 value")
+    bits2, norms2 = qjl.qjl_quantize_keys(K, S)
+    assert torch.equal(bits, bits2) and torch.equal(norms, norms2)      # deterministic
+
+
+def test_quantize_zero_and_tiny_keys():
+    """||k|| = 0 -> norm 0 and all bits 1 (sign(0) := +1); -k flips every bit."""
+    say("[quantize] zero keys and negation")
+    K = inputs.make_keys(1, 1, 64, 128, torch.bfloat16, 5, DEV)
+    K[0, 0, 3] = 0
+    K[0, 0, 40] = 0
+    S = qjl.qjl_make_sketch(3, 256, 128, torch.bfloat16, DEV)
+    bits, norms = qjl.qjl_quantize_keys(K, S)
+    assert bits[0, 0, 3].eq(255).all() and bits[0, 0, 40].eq(255).all()
+    assert norms[0, 0, 3] == 0 and norms[0, 0, 40] == 0
+    nb, nn = qjl.qjl_quantize_keys(-K, S)
+    keep = torch.ones(64, dtype=torch.bool, device=DEV)
+    keep[3] = keep[40] = False
+    assert torch.equal(nb[0, 0, keep], ~bits[0, 0, keep]) and torch.equal(nn, norms)
+    K32 = K.float()
+    S32 = S.float()
+    b32, n32 = qjl.qjl_quantize_keys(K32, S32)                          # same values via the fp32 path
+    bad, flips, _ = bits_report(b32.cpu().numpy(), inputs.to_f64(K32), inputs.to_f64(S32))
+    assert bad == 0
+    assert b32[0, 0, 3].eq(255).all() and n32[0, 0, 3] == 0
+
+
+# ------------------------------------------------------------------ b1: project the query
+@pytest.mark.parametrize("dt,B,Hq,d,m", [("bf16", 1, 32, 128, 256), ("f32", 1, 1, 128, 256),
+                                         ("f16", 3, 5, 128, 512), ("bf16", 2, 3, 128, 40),
+                                         ("f32", 2, 2, 24, 40), ("bf16", 1, 4, 64, 96)])
+def test_project_query_parity(dt, B, Hq, d, m):
+    say(f"[project] dt={dt} B={B} Hq={Hq} d={d} m={m}")
+    Q = inputs.make_normal((B, Hq, d), DT[dt], 21, DEV)
+    S = qjl.qjl_make_sketch(8, m, d, DT[dt], DEV)
+    SQ = qjl.qjl_project_query(Q, S).cpu().numpy()
+    ref = orc.project_query(inputs.to_f64(Q), inputs.to_f64(S))
+    scale = np.linalg.norm(inputs.to_f64(Q), axis=-1, keepdims=True) * np.linalg.norm(inputs.to_f64(S), axis=1)
+    assert np.all(np.abs(SQ - ref) <= 1e-5 * scale)
+
+
+# ------------------------------------------------------------------ b2: scores
+@pytest.mark.parametrize("B,Hq,Hkv,n,m,scale", [
+    (1, 1, 1, 1024, 256, 1.0), (1, 4, 4, 3000, 256, 0.0884), (2, 8, 2, 777, 256, 0.0884),
+    (1, 6, 3, 300, 512, 1.0), (1, 3, 3, 65, 128, 0.5), (1, 8, 1, 2500, 128, 1.0),
+    (1, 2, 1, 1, 256, 1.0)])
+def test_scores_parity(B, Hq, Hkv, n, m, scale):
+    say(f"[scores] B={B} Hq={Hq} Hkv={Hkv} n={n} m={m} scale={scale}")
+    d = 128
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 31 + n, DEV)
+    Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 32, DEV)
+    S = qjl.qjl_make_sketch(9, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    SQ64 = orc.project_query(inputs.to_f64(Q), inputs.to_f64(S))
+    SQ_d = torch.from_numpy(SQ64.astype(np.float32)).to(DEV)
+    got = qjl.qjl_scores(SQ_d, bits_d, nu_d, scale).cpu().numpy()
+    ref = orc.estimate_scores(SQ64.astype(np.float32).astype(np.float64), bits, nu16, scale)
+    worst = assert_scores(got, ref)
+    say(f"  worst error / tolerance = {worst:.3g}")
+
+
+# ------------------------------------------------------------------ c1-c3: decode attention
+DECODE_CASES = [
+    # dt, B, Hq, Hkv, n, m, scale
+    ("f32", 1, 1, 1, 1024, 256, 1.0),            # config 1
+    ("bf16", 1, 4, 4, 4096, 256, 0.0884),        # config-2 heads
+    ("bf16", 2, 8, 2, 1500, 256, 0.0884),        # GQA x4, ragged
+    ("bf16", 1, 8, 4, 333, 256, 1.0),            # GQA x2, paper-literal scale
+    ("bf16", 1, 3, 1, 700, 256, 0.0884),         # GQA x3 -> one head at a time
+    ("f16", 1, 4, 1, 260, 512, 0.0884),          # m=512, fp16
+    ("bf16", 1, 4, 1, 129, 128, 0.0884),         # m=128
+    ("bf16", 1, 2, 2, 1, 256, 1.0),              # n = 1: out = v_1
+    ("bf16", 1, 1, 1, 63, 256, 0.0884),
+    ("bf16", 1, 1, 1, 65, 256, 0.0884),
+    ("bf16", 1, 2, 1, 20000, 256, 0.0884),       # many chunks
+]
+
+
+@pytest.mark.parametrize("dt,B,Hq,Hkv,n,m,scale", DECODE_CASES)
+def test_decode_attention_parity(dt, B, Hq, Hkv, n, m, scale):
+    say(f"[decode] dt={dt} B={B} Hq={Hq} Hkv={Hkv} n={n} m={m} scale={scale}")
+    d = 128
+    K = inputs.make_keys(B, Hkv, n, d, DT[dt], 41 + n, DEV, outliers=0 if dt == "f32" else 4)
+    Q = inputs.make_normal((B, Hq, d), DT[dt], 42, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), DT[dt], 43, DEV)
+    S = qjl.qjl_make_sketch(10, m, d, DT[dt], DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    ref = orc.decode_attention(inputs.to_f64(Q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), scale)
+    out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale)
+    err = assert_attention(out.cpu().numpy(), ref)
+    say(f"  max abs error {err:.3g}")
+    # a second call on the same workspace-free path gives the same bits
+    out2 = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale)
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("splits", [1, 2, 7, 64])
+def test_decode_split_count_does_not_matter(splits, monkeypatch):
+    say(f"[decode] forced chunk count {splits}")
+    B, Hq, Hkv, n, d, m = 1, 8, 2, 5000, 128, 256
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 51, DEV)
+    Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 52, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 53, DEV)
+    S = qjl.qjl_make_sketch(11, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    ref = orc.decode_attention(inputs.to_f64(Q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), 0.0884)
+    monkeypatch.setenv("QJL_DECODE_SPLITS", str(splits))
+    ws = torch.full((qjl.qjl_decode_workspace_bytes(B, Hq, Hkv, n, d, m),), 0xAB, dtype=torch.uint8,
+                    device=DEV)                       # dirty workspace: contents must not matter
+    for _ in range(3):                                # counters must be usable call after call
+        out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, 0.0884, workspace=ws)
+        assert_attention(out.cpu().numpy(), ref)
+
+
+def test_decode_degenerate_queries():
+    """q = 0 -> uniform weights -> out = mean of V (an oracle pin, checked on the GPU too)."""
+    say("[decode] q = 0")
+    B, Hq, Hkv, n, d, m = 1, 4, 4, 999, 128, 256
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 61, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 63, DEV)
+    S = qjl.qjl_make_sketch(12, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), _ = oracle_cache(K, S)
+    Q = torch.zeros((B, Hq, d), dtype=torch.bfloat16, device=DEV)
+    out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, 1.0).cpu().numpy()
+    assert_attention(out, inputs.to_f64(V).mean(axis=2))
+
+
+def test_pipeline_end_to_end_config1():
+    """Config 1 run as a chain on the GPU (quantize -> project -> scores, and
+    quantize -> decode) against the same chain in the oracle."""
+    w = inputs.WORKLOADS["c1_single_head"]
+    say(f"[chain] {w.name}")
+    K, Q, V = inputs.make_workload_tensors(w, DEV)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, DEV)
+    K64, Q64, V64, S64 = map(inputs.to_f64, (K, Q, V, S))
+    bits_d, nu_d = qjl.qjl_quantize_keys(K, S)
+    bad, flips, inband = bits_report(bits_d.cpu().numpy(), K64, S64)
+    say(f"  bits: {bad} outside band, {flips} flips of {inband} near-zero entries")
+    assert bad == 0
+    if flips:
+        pytest.skip(f"{flips} near-zero sign decisions differ; the chained comparison needs equal codes")
+    bits, nu16, _ = orc.quantize_keys(K64, S64)
+    SQ = qjl.qjl_project_query(Q, S)
+    sc = qjl.qjl_scores(SQ, bits_d, nu_d, w.scale).cpu().numpy()
+    ref_sc = orc.estimate_scores(orc.project_query(Q64, S64), bits, nu16, w.scale)
+    # the GPU's norms may sit one binary16 step from the oracle's: allow for it
+    step = 2.0 ** -10
+    rms = np.sqrt(np.mean(ref_sc ** 2))
+    assert np.all(np.abs(sc - ref_sc) <= (1e-3 + step) * np.maximum(np.abs(ref_sc), 1e-2 * rms))
+    out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, w.scale).cpu().numpy()
+    ref = orc.decode_attention(Q64, S64, bits_d.cpu().numpy(), nu_d.cpu().numpy(), V64, w.scale)
+    assert_attention(out, ref)
+
+
+# ------------------------------------------------------------------ full-size configurations, sampled
+def _sample_units(B, Hkv, count, seed):
+    rng = np.random.default_rng(seed)
+    flat = rng.choice(B * Hkv, size=min(count, B * Hkv), replace=False)
+    return [(int(u // Hkv), int(u % Hkv)) for u in sorted(flat)]
+
+
+@pytest.mark.parametrize("name,units", [("c2_llama2_7b_decode_4k", 32), ("c3_long_context_b4_32k", 6),
+                                        ("c5a_llama3_8b_gqa_b1_128k", 2), ("c5b_llama3_8b_gqa_b16_8k", 6)])
+def test_full_size_decode_sampled(name, units):
+    """The benchmark's launch configuration at full size.  The oracle handles the
+    sampled (batch, kv head) units only: their keys are quantized by the oracle,
+    the GPU consumes exactly those codes for them, and the attention outputs of
+    all query heads of those units are compared."""
+    w = inputs.WORKLOADS[name]
+    say(f"[full decode] {name}")
+    K, Q, V = inputs.make_workload_tensors(w, DEV)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, DEV)
+    S64, Q64 = inputs.to_f64(S), inputs.to_f64(Q)
+    bits_d, nu_d = qjl.qjl_quantize_keys(K, S)
+    G = w.q_heads // w.kv_heads
+    picked = _sample_units(w.batch, w.kv_heads, units, w.data_seed)
+    refs = {}
+    tot_bad = tot_flip = 0
+    for (b, g) in picked:
+        K64 = inputs.to_f64(K[b, g])[None, None]
+        bad, flips, _ = bits_report(bits_d[b, g].cpu().numpy()[None, None], K64, S64)
+        tot_bad += bad
+        tot_flip += flips
+        assert_norms(nu_d[b, g].cpu().numpy()[None, None], K64)
+        bits, nu16, _ = orc.quantize_keys(K64, S64)
+        bits_d[b, g] = torch.from_numpy(bits[0, 0]).to(DEV)            # both sides use the oracle's code
+        nu_d[b, g] = torch.from_numpy(nu16[0, 0]).to(DEV)
+        refs[(b, g)] = orc.decode_attention(Q64[b:b + 1, g * G:(g + 1) * G], S64, bits, nu16,
+                                            inputs.to_f64(V[b, g])[None, None], w.scale)[0]
+        say(f"  unit b={b} kv={g}: oracle done")
+    say(f"  quantize on sampled units: {tot_bad} outside band, {tot_flip} near-zero flips")
+    assert tot_bad == 0
+    del K
+    out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, w.scale).cpu().numpy()
+    worst = 0.0
+    for (b, g), ref in refs.items():
+        worst = max(worst, assert_attention(out[b, g * G:(g + 1) * G], ref))
+    assert np.all(np.isfinite(out))
+    # property that holds for every head at any size: outputs are convex
+    # combinations of the values, so they lie inside V's per-channel range
+    vmax = V.float().amax(dim=2).cpu().numpy().repeat(G, axis=1)
+    vmin = V.float().amin(dim=2).cpu().numpy().repeat(G, axis=1)
+    assert np.all(out <= vmax + 1e-3) and np.all(out >= vmin - 1e-3)
+    say(f"  worst attention error over {len(refs) * G} heads: {worst:.3g}")
+
+
+def test_full_size_prefill_quantize_sampled():
+    """Config 4 at full size (2,097,152 keys, m = 512): sampled rows against the oracle,
+    plus whole-tensor properties (norm range, bit balance)."""
+    w = inputs.WORKLOADS["c4_prefill_quantize_64k"]
+    say(f"[full quantize] {w.name}")
+    K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, DEV, w.outliers)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, DEV)
+    bits_d, nu_d = qjl.qjl_quantize_keys(K, S)
+    torch.cuda.synchronize()
+    S64 = inputs.to_f64(S)
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([rng.integers(0, w.kv_heads * w.n, size=6000),
+                                     np.arange(0, 64), np.arange(w.kv_heads * w.n - 64, w.kv_heads * w.n),
+                                     np.arange(w.n - 40, w.n + 40)]))   # ends and a head boundary
+    idx = torch.from_numpy(rows).to(DEV)
+    Kr = inputs.to_f64(K.view(-1, w.d)[idx])[None, None]
+    bad, flips, inband = bits_report(bits_d.view(-1, w.m // 8)[idx].cpu().numpy()[None, None], Kr, S64)
+    say(f"  {rows.size} sampled rows: {bad} outside band, {flips} flips of {inband} near-zero entries")
+    assert bad == 0
+    assert_norms(nu_d.view(-1)[idx].cpu().numpy()[None, None], Kr)
+    # whole tensor: norms equal the fp32 norm computed by torch within fp16 rounding; bits are balanced
+    ref_n = K.float().norm(dim=-1)
+    assert torch.all((nu_d.float() - ref_n).abs() <= 1e-3 * ref_n)
+    ones = 0
+    for h in range(w.kv_heads):
+        ones += int(torch.sum(_popcount8(bits_d[0, h])))
+    frac = ones / (w.kv_heads * w.n * w.m)
+    say(f"  fraction of +1 signs: {frac:.5f}")
+    assert abs(frac - 0.5) < 5e-3
+
+
+_POP = None
+
+
+def _popcount8(t: torch.Tensor) -> torch.Tensor:
+    global _POP
+    if _POP is None:
+        _POP = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=DEV)
+    return _POP[t.long()]
