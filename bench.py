@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the QJL hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+
+A "step" is one decode step of the Llama-2-7B-shaped workload (batch 1, 32
+heads, d = 128, m = 256, context 4096; keys already quantized and everything
+resident in HBM): project the query, estimate all scores, softmax, aggregate
+the bf16 values -- one call of qjl_decode_attention.  The headline `value` is
+keys (= batch x kv-head x token triples) per second over exactly K steps; the
+steps are replayed from a HIP graph so that the host's launch cost does not
+hide the GPU time (the eager rate is reported next to it).
+
+The `roofline` object is for the attention kernel of that step: algorithmic
+bytes per launch (290 B per key: 32 B code + 2 B norm + 256 B values) over the
+kernel's mean duration measured with HIP events recorded around the kernel
+itself (qjl_decode_attention_timed).  `other_workloads` repeats the
+measurement for the long-context, GQA and prefill-quantize configurations.
+`cpu_baseline` times the CPU oracle on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+
+
+class HipEvents:
+    """hipEvent_t handles through ctypes (torch's events only see torch's own records)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self) -> int:
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate -> {rc}")
+        return ev.value
+
+    def record(self, ev: int, stream: int) -> None:
+        rc = self.hip.hipEventRecord(ev, stream)
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord -> {rc}")
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime -> {rc}")
+        return float(ms.value)
+
+    def destroy(self, ev: int) -> None:
+        self.hip.hipEventDestroy(ev)
+
+
+def decode_bytes_per_key(w) -> int:
+    """Algorithmic HBM bytes per (batch, kv head, token): code + norm + one row of V."""
+    return w.m // 8 + 2 + w.d * 2
+
+
+def load_traffic(name: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except Exception:
+        return None
+
+
+def prepare_decode(qjl, inputs, w, dev):
+    import torch
+    K, Q, V = inputs.make_workload_tensors(w, dev)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    bits, norms = qjl.qjl_quantize_keys(K, S)       # untimed: the cache already exists at decode time
+    del K
+    ws = torch.empty((qjl.qjl_decode_workspace_bytes(w.batch, w.q_heads, w.kv_heads, w.n, w.d, w.m, w.dtype),),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty((w.batch, w.q_heads, w.d), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    return dict(Q=Q, S=S, bits=bits, norms=norms, V=V, ws=ws, out=out)
+
+
+def run_decode(qjl, t, w, events=None):
+    qjl.qjl_decode_attention(t["Q"], t["S"], t["bits"], t["norms"], t["V"], w.scale, out=t["out"],
+                             workspace=t["ws"], events=events)
+
+
+def time_decode(qjl, ev, w, t, steps, warmup, graph_batch=None):
+    """Returns dict(ms_graph, ms_eager, kernel_ms) for one workload."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        run_decode(qjl, t, w)
+    torch.cuda.synchronize()
+    # ---- eager: K library calls back to back
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_decode(qjl, t, w)
+    torch.cuda.synchronize()
+    ms_eager = (time.perf_counter() - t0) * 1e3 / steps
+    # ---- HIP graph holding `gb` steps, replayed steps/gb times (exactly `steps` steps)
+    gb = graph_batch or next(g for g in (50, 25, 20, 10, 5, 4, 2, 1) if steps % g == 0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_decode(qjl, t, w)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(gb):
+            run_decode(qjl, t, w)
+    for _ in range(max(1, warmup // gb)):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps // gb):
+        g.replay()
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    # ---- the attention kernel alone: events recorded around it inside the library call
+    nk = min(steps, 200)
+    pairs = [(ev.create(), ev.create()) for _ in range(nk)]
+    for a, b in pairs:
+        run_decode(qjl, t, w, events=(a, b))
+    torch.cuda.synchronize()
+    durs = sorted(ev.elapsed_ms(a, b) for a, b in pairs)
+    for a, b in pairs:
+        ev.destroy(a)
+        ev.destroy(b)
+    kernel_ms = sum(durs) / len(durs)
+    return dict(ms_graph=ms_graph, ms_eager=ms_eager, kernel_ms=kernel_ms, kernel_ms_median=durs[len(durs) // 2],
+                graph_batch=gb)
+
+
+def decode_record(w, r):
+    algo_bytes = decode_bytes_per_key(w) * w.key_heads
+    achieved = algo_bytes / (r["kernel_ms"] * 1e-3) / 1e9
+    return {
+        "workload": w.name,
+        "metric": "decode keys/s/GPU",
+        "value": w.key_heads / (r["ms_graph"] * 1e-3),
+        "ms_per_step": r["ms_graph"],
+        "ms_per_step_eager": r["ms_eager"],
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(w.name),
+                     "kernel": "decode_kernel", "kernel_ms": r["kernel_ms"],
+                     "kernel_ms_median": r["kernel_ms_median"], "algorithmic_bytes": algo_bytes},
+    }
+
+
+def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
+    import torch
+    K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, dev, w.outliers)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    bits = torch.empty((w.batch, w.kv_heads, w.n, w.m // 8), dtype=torch.uint8, device=dev)
+    norms = torch.empty((w.batch, w.kv_heads, w.n), dtype=torch.float16, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        qjl.qjl_quantize_keys(K, S, bits, norms)
+    torch.cuda.synchronize()
+    a, b = ev.create(), ev.create()
+    ev.record(a, stream)
+    for _ in range(steps):
+        qjl.qjl_quantize_keys(K, S, bits, norms)
+    ev.record(b, stream)
+    ms = ev.elapsed_ms(a, b) / steps          # one kernel per call, back to back: events bracket the kernels
+    ev.destroy(a)
+    ev.destroy(b)
+    rows = w.batch * w.kv_heads * w.n
+    flops = 2.0 * w.d * w.m * rows
+    achieved = flops / (ms * 1e-3) / 1e12
+    algo_bytes = rows * (w.d * 2 + w.m // 8 + 2)
+    return {
+        "workload": w.name,
+        "metric": "prefill quantize tokens/s",
+        "value": w.batch * w.n / (ms * 1e-3),
+        "rows_per_s": rows / (ms * 1e-3),
+        "ms_per_step": ms,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": load_traffic(w.name),
+                     "kernel": "quantize_mfma_kernel", "kernel_ms": ms, "flops": flops,
+                     "algorithmic_bytes": algo_bytes, "hbm_GBs": algo_bytes / (ms * 1e-3) / 1e9},
+    }
+
+
+def cpu_baseline(inputs, w, budget_s=12.0):
+    """The oracle, as it stands, on the host cores: the same decode step
+    (project -> scores -> softmax -> values) on the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info, threadpool_limits
+    from oracle import qjl_oracle as orc
+    K, Q, V = inputs.make_workload_tensors(w, "cpu")
+    S = orc.gaussian_sketch(w.sketch_seed, w.m, w.d, "bf16")
+    K64, Q64, V64 = inputs.to_f64(K), inputs.to_f64(Q), inputs.to_f64(V)
+    bits, nu16, _ = orc.quantize_keys(K64, S)             # untimed, as on the GPU
+    cores = min(16, os.cpu_count() or 1)
+    with threadpool_limits(limits=cores):
+        orc.decode_attention(Q64, S, bits, nu16, V64, w.scale)   # warm-up
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            orc.decode_attention(Q64, S, bits, nu16, V64, w.scale)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el >= budget_s or reps >= 50:
+                break
+        used = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": w.key_heads * reps / el, "unit": "keys/s", "cores": int(min(cores, used)), "kind": "oracle",
+            "sample": f"{reps} full decode steps of {w.name} (all {w.key_heads} keys each), numpy float64, "
+                      f"{el:.1f} s of CPU work"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the hot path has no cross-GPU step); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2406_03482_amd as qjl
+    from paper_2406_03482_amd import inputs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    qjl.lib()                                   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    ev = HipEvents()
+
+    w = inputs.WORKLOADS["c2_llama2_7b_decode_4k"]
+    t = prepare_decode(qjl, inputs, w, dev)
+    r = time_decode(qjl, ev, w, t, args.steps, args.warmup)
+    head = decode_record(w, r)
+    del t
+    torch.cuda.empty_cache()
+
+    line = {
+        "metric": "decode keys/s/GPU",
+        "value": head["value"],
+        "unit": "keys/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "ms_per_step_eager": head["ms_per_step_eager"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
+                   "context": w.n, "d": w.d, "m": w.m, "launch": f"hip graph of {r['graph_batch']} steps"},
+        "roofline": head["roofline"],
+    }
+
+    if not args.no_extra:
+        extra = []
+        for name, steps, warm in [("c3_long_context_b4_32k", 100, 20), ("c5a_llama3_8b_gqa_b1_128k", 200, 20),
+                                  ("c5b_llama3_8b_gqa_b16_8k", 200, 20)]:
+            wx = inputs.WORKLOADS[name]
+            tx = prepare_decode(qjl, inputs, wx, dev)
+            extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm)))
+            del tx
+            torch.cuda.empty_cache()
+        extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
+        line["other_workloads"] = extra
+
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(inputs, w)
+    else:
+        line["cpu_baseline"] = None
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
