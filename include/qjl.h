@@ -107,7 +107,7 @@ int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits,
 
 /*
  * Bytes of device scratch qjl_decode_attention needs for this shape (query
- * projections, per-split softmax partials, completion counters).  Returns 0
+ * projections and per-chunk softmax partials).  Returns 0
  * for an invalid or unsupported shape.  Host only.
  */
 size_t qjl_decode_workspace_bytes(const qjl_shape* shape);

@@ -62,7 +62,7 @@ int qjl_project_query(const qjl_shape* shape, const void* Q, const void* S, floa
   if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(SQ)) return QJL_ERR_INVALID_ARG;
   if ((long)shape->batch * shape->q_heads > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   return launch_project(shape->batch * shape->q_heads, shape->d, shape->m, shape->dtype, Q, S, SQ,
-                        nullptr, 0, static_cast<hipStream_t>(stream));
+                        static_cast<hipStream_t>(stream));
 }
 
 int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits, const uint16_t* norms,

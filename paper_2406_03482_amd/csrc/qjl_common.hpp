@@ -129,7 +129,7 @@ int launch_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, hipStrea
 int launch_quantize(const qjl_shape& sh, const void* K, const void* S, uint8_t* bits,
                     uint16_t* norms, hipStream_t st);
 int launch_project(int rows, int d, int m, int dtype, const void* Q, const void* S, float* SQ,
-                   uint32_t* zero_words, int n_zero_words, hipStream_t st);
+                   hipStream_t st);
 int launch_scores(const qjl_shape& sh, const float* SQ, const uint8_t* bits,
                   const uint16_t* norms, float* out, hipStream_t st);
 
@@ -139,8 +139,6 @@ struct decode_plan {
   int chunk;         // keys per chunk (multiple of 64)
   size_t off_sq;     // byte offsets inside the workspace
   size_t off_part;
-  size_t off_cnt;
-  size_t n_cnt;      // number of 32-bit completion counters
   size_t total;      // bytes
 };
 bool plan_decode(const qjl_shape& sh, decode_plan* plan);

@@ -5,8 +5,8 @@
 // HBM-bound: per key and KV head the kernel reads m/8 code bytes, a 2-byte
 // norm and one row of V, nothing else of size.  The context is cut into
 // chunks (one workgroup each); every wave keeps a running (max, sum, o[d])
-// and the partial results are merged wave -> workgroup -> last workgroup of
-// the unit with the usual max/sum-of-exponentials rescaling.
+// and the partial results are merged wave -> workgroup -> (a small second
+// kernel) across chunks with the usual max/sum-of-exponentials rescaling.
 #include "qjl_common.hpp"
 #include "qjl_lut.hpp"
 
@@ -33,7 +33,6 @@ struct decode_args {
   const uint16_t* norms;  // [B,Hkv,n]
   const void* V;          // [B,Hkv,n,128]
   float* part;            // [B,Hq,nsplit,132]
-  uint32_t* cnt;          // [units]
   float* out;             // [B,Hq,128]
   int n, q_heads, kv_heads, groups_per_kv;
   int nsplit, chunk;
@@ -254,30 +253,26 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
       if (ch == 0) { rec[0] = mx; rec[1] = L; }
     }
   }
-  if (a.nsplit == 1) return;
+}
 
-  // ---- the workgroup that finishes last for this unit merges the chunks
-  __shared__ int s_last;
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_last = (atomicAdd(&a.cnt[unit], 1u) == (uint32_t)(a.nsplit - 1)) ? 1 : 0;
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  for (int idx = tid; idx < GT * kD; idx += kNW * 64) {
-    const int g = idx >> 7, ch = idx & 127;
-    const float* base = a.part + (hq0 + g) * (size_t)a.nsplit * kPartStride;
-    float mx = -INFINITY;
-    for (int s2 = 0; s2 < a.nsplit; ++s2) mx = fmaxf(mx, base[(size_t)s2 * kPartStride]);
-    float L = 0.f, O = 0.f;
-    for (int s2 = 0; s2 < a.nsplit; ++s2) {
-      const float* rec = base + (size_t)s2 * kPartStride;
-      const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
-      L = fmaf(rec[1], f, L);
-      O = fmaf(rec[4 + ch], f, O);
-    }
-    a.out[(hq0 + g) * kD + ch] = O / L;
+// Merge the per-chunk records of one query head: out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+// A kernel of its own: the kernel boundary makes the records of all workgroups
+// visible without device-wide fences inside the streaming kernel.
+__global__ void __launch_bounds__(kD) combine_kernel(const float* __restrict__ part,
+                                                     float* __restrict__ out, int nsplit) {
+  const size_t head = blockIdx.x;
+  const int ch = threadIdx.x;
+  const float* base = part + head * (size_t)nsplit * kPartStride;
+  float mx = -INFINITY;
+  for (int s2 = 0; s2 < nsplit; ++s2) mx = fmaxf(mx, base[(size_t)s2 * kPartStride]);
+  float L = 0.f, O = 0.f;
+  for (int s2 = 0; s2 < nsplit; ++s2) {
+    const float* rec = base + (size_t)s2 * kPartStride;
+    const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
+    L = fmaf(rec[1], f, L);
+    O = fmaf(rec[4 + ch], f, O);
   }
+  out[head * kD + ch] = O / L;
 }
 
 template <typename T, int GT, int MW>
@@ -370,9 +365,6 @@ bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
   off = align_up(off + (size_t)sh.batch * sh.q_heads * sh.m * sizeof(float), 256);
   plan->off_part = off;
   off = align_up(off + (size_t)sh.batch * sh.q_heads * nsplit * kPartStride * sizeof(float), 256);
-  plan->off_cnt = off;
-  plan->n_cnt = (size_t)units;
-  off = align_up(off + (size_t)units * sizeof(uint32_t), 256);
   plan->total = off;
   return true;
 }
@@ -382,15 +374,13 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
                   void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
   float* SQ = reinterpret_cast<float*>(ws + plan.off_sq);
-  uint32_t* cnt = reinterpret_cast<uint32_t*>(ws + plan.off_cnt);
-  // kernel 1: S q for every query head, and clear the completion counters
-  int rc = launch_project(sh.batch * sh.q_heads, sh.d, sh.m, sh.dtype, Q, S, SQ, cnt,
-                          (int)plan.n_cnt, st);
+  // kernel 1: S q for every query head
+  int rc = launch_project(sh.batch * sh.q_heads, sh.d, sh.m, sh.dtype, Q, S, SQ, st);
   if (rc != QJL_OK) return rc;
   decode_args a;
   a.SQ = SQ; a.bits = bits; a.norms = norms; a.V = V;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);
-  a.cnt = cnt; a.out = out;
+  a.out = out;
   a.n = sh.n; a.q_heads = sh.q_heads; a.kv_heads = sh.kv_heads;
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
@@ -405,7 +395,11 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
     default: rc = launch_m<bf16_t>(sh, plan, a, st); break;
   }
   if (rc == QJL_OK && ev_after) rc = hip_status(hipEventRecord(ev_after, st));
-  return rc;
+  if (rc != QJL_OK || plan.nsplit == 1) return rc;
+  // kernel 3: merge the chunks
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(sh.batch * sh.q_heads)), dim3(kD), 0, st,
+                     a.part, out, plan.nsplit);
+  return launch_status();
 }
 
 }  // namespace qjl

@@ -11,11 +11,9 @@ namespace {
 template <typename T>
 __global__ void __launch_bounds__(256)
 project128_kernel(const void* __restrict__ Q, const void* __restrict__ S, float* __restrict__ SQ,
-                  int m, uint32_t* __restrict__ zero_words, int n_zero_words) {
+                  int m) {
   const int row = blockIdx.x;                 // (b, hq) flattened
   const int tid = threadIdx.x;
-  // the first workgroups also clear the caller's completion counters
-  for (int i = row * 256 + tid; i < n_zero_words; i += gridDim.x * 256) zero_words[i] = 0u;
 
   const int c = tid & 15;                     // 8-element slice of the row
   const int r = tid >> 4;                     // 0..15: row inside a pass of 16 rows
@@ -38,11 +36,9 @@ project128_kernel(const void* __restrict__ Q, const void* __restrict__ S, float*
 template <typename T>
 __global__ void __launch_bounds__(256)
 project_generic_kernel(const void* __restrict__ Q, const void* __restrict__ S,
-                       float* __restrict__ SQ, int d, int m, uint32_t* __restrict__ zero_words,
-                       int n_zero_words) {
+                       float* __restrict__ SQ, int d, int m) {
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
-  for (int i = row * 256 + tid; i < n_zero_words; i += gridDim.x * 256) zero_words[i] = 0u;
   for (int i = tid; i < m; i += 256) {
     float acc = 0.f;
     for (int t = 0; t < d; ++t)
@@ -52,24 +48,23 @@ project_generic_kernel(const void* __restrict__ Q, const void* __restrict__ S,
 }
 
 template <typename T>
-int launch_t(int rows, int d, int m, const void* Q, const void* S, float* SQ, uint32_t* zw, int nzw,
-             hipStream_t st) {
+int launch_t(int rows, int d, int m, const void* Q, const void* S, float* SQ, hipStream_t st) {
   dim3 grid((unsigned)rows), block(256);
   if (d == 128)
-    hipLaunchKernelGGL(project128_kernel<T>, grid, block, 0, st, Q, S, SQ, m, zw, nzw);
+    hipLaunchKernelGGL(project128_kernel<T>, grid, block, 0, st, Q, S, SQ, m);
   else
-    hipLaunchKernelGGL(project_generic_kernel<T>, grid, block, 0, st, Q, S, SQ, d, m, zw, nzw);
+    hipLaunchKernelGGL(project_generic_kernel<T>, grid, block, 0, st, Q, S, SQ, d, m);
   return launch_status();
 }
 
 }  // namespace
 
 int launch_project(int rows, int d, int m, int dtype, const void* Q, const void* S, float* SQ,
-                   uint32_t* zero_words, int n_zero_words, hipStream_t st) {
+                   hipStream_t st) {
   switch (dtype) {
-    case QJL_F32: return launch_t<f32_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
-    case QJL_F16: return launch_t<f16_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
-    default: return launch_t<bf16_t>(rows, d, m, Q, S, SQ, zero_words, n_zero_words, st);
+    case QJL_F32: return launch_t<f32_t>(rows, d, m, Q, S, SQ, st);
+    case QJL_F16: return launch_t<f16_t>(rows, d, m, Q, S, SQ, st);
+    default: return launch_t<bf16_t>(rows, d, m, Q, S, SQ, st);
   }
 }
 
