@@ -235,6 +235,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
+                    "metric is quoted on), c3, c5a, c5b (decode) or c4 (prefill quantize); for profiling single kernels")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -253,17 +255,26 @@ def main() -> int:
     dev = "cuda:0"
     ev = HipEvents()
 
-    w = inputs.WORKLOADS["c2_llama2_7b_decode_4k"]
-    t = prepare_decode(qjl, inputs, w, dev)
-    r = time_decode(qjl, ev, w, t, args.steps, args.warmup)
-    head = decode_record(w, r)
-    del t
+    names = {k.split("_")[0]: k for k in inputs.WORKLOADS}
+    if args.workload not in names or args.workload == "c1":
+        print(f"bench.py: unknown workload {args.workload!r}", file=sys.stderr)
+        return 2
+    w = inputs.WORKLOADS[names[args.workload]]
+    if args.workload == "c4":
+        head = bench_quantize(qjl, inputs, ev, w, dev, args.steps, args.warmup)
+        head["ms_per_step_eager"] = head["ms_per_step"]
+        r = {"graph_batch": 0}
+    else:
+        t = prepare_decode(qjl, inputs, w, dev)
+        r = time_decode(qjl, ev, w, t, args.steps, args.warmup)
+        head = decode_record(w, r)
+        del t
     torch.cuda.empty_cache()
 
     line = {
-        "metric": "decode keys/s/GPU",
+        "metric": head["metric"],
         "value": head["value"],
-        "unit": "keys/s",
+        "unit": "tokens/s" if args.workload == "c4" else "keys/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -275,7 +286,7 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
-                   "context": w.n, "d": w.d, "m": w.m, "launch": f"hip graph of {r['graph_batch']} steps"},
+                   "context": w.n, "d": w.d, "m": w.m, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
         "roofline": head["roofline"],
     }
 
@@ -291,7 +302,7 @@ def main() -> int:
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         line["other_workloads"] = extra
 
-    if not args.no_cpu:
+    if not args.no_cpu and args.workload != "c4":
         line["cpu_baseline"] = cpu_baseline(inputs, w)
     else:
         line["cpu_baseline"] = None

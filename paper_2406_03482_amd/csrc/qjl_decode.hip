@@ -25,7 +25,10 @@ constexpr size_t decode_lds_bytes(int gt, int m) { return (size_t)gt * m * 37 * 
 // Waves per workgroup: small tables let four workgroups share the 160 KiB of a
 // CU (four waves each); larger tables mean one or two workgroups per CU, which
 // then get eight waves so that every SIMD still has two to switch between.
-constexpr int decode_waves(int gt, int m) { return decode_lds_bytes(gt, m) <= 40 * 1024 ? 4 : 8; }
+// (fp32 values need twice the registers per wave, so they stay at four waves.)
+constexpr int decode_waves(int gt, int m, int elem_bytes) {
+  return (decode_lds_bytes(gt, m) <= 40 * 1024 || elem_bytes == 4) ? 4 : 8;
+}
 
 struct decode_args {
   const float* SQ;        // [B,Hq,m]
@@ -43,7 +46,7 @@ struct decode_args {
 template <typename T> struct vtile {
   static constexpr int kRegs = 1;  // uint4 per 8 elements
   uint4 r;
-  __device__ __forceinline__ void load(const void* V, size_t elem) {
+  __device__ __forceinline__ void load(const void* V, uint32_t elem) {
     r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(V) + elem);
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
@@ -54,7 +57,7 @@ template <typename T> struct vtile {
 // ... or 32 bytes (fp32).
 template <> struct vtile<f32_t> {
   float4 a, b;
-  __device__ __forceinline__ void load(const void* V, size_t elem) {
+  __device__ __forceinline__ void load(const void* V, uint32_t elem) {
     const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(V) + elem);
     a = p[0]; b = p[1];
   }
@@ -64,8 +67,10 @@ template <> struct vtile<f32_t> {
 };
 
 template <typename T, int GT, int MW>
-__global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(decode_args a) {
-  constexpr int kNW = decode_waves(GT, MW * 32);
+__global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
+                                  T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
+decode_kernel(decode_args a) {
+  constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   extern __shared__ float4 smem4[];
   float* smem = reinterpret_cast<float*>(smem4);
   constexpr int M = MW * 32;
@@ -82,7 +87,7 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps block indices in SGPRs
   const int unit = blockIdx.x / a.nsplit;
   const int split = blockIdx.x - unit * a.nsplit;
   const int gg = unit % a.groups_per_kv;
@@ -91,11 +96,6 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
   const int G = a.groups_per_kv * GT;
   const size_t hq0 = (size_t)b * a.q_heads + (size_t)kvh * G + (size_t)gg * GT;
 
-  for (int e = tid; e < GT * M; e += kNW * 64) sq[e] = a.SQ[hq0 * M + e];
-  __syncthreads();
-  build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
-  // build_lut ends with a barrier: nobody reads `nib` any more.
-
   const int k_begin = split * a.chunk;
   const int k_end = min(a.n, k_begin + a.chunk);
   const size_t row0 = (size_t)bk * a.n;
@@ -103,40 +103,48 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
   const int r = lane >> 4;                            // row of a 4-row V pass
   const int c = lane & 15;                            // 8-channel slice
 
-  float m_run[GT], l_lane[GT], acc[GT][8];
-#pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    m_run[g] = -INFINITY;
-    l_lane[g] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  }
-
+  // ---- first block of this wave: start its HBM reads before anything else, so
+  // that they are in flight while the tables are built.  Rows past the chunk
+  // end are clamped (never out of bounds); their weight is 0.
   int k0 = k_begin + wave * 64;
   uint32_t wcur[MW];
   float ncur = 0.f;
+  vtile<T> v[16];
+  // row (4i + r) of the block starting at key kb: uniform base pointer + a
+  // 32-bit lane offset, the row clamped to the last key of the chunk
+  auto issue_v = [&](int i, int kb, int last_row) {
+    const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * T::bytes);
+    const int rr = min(4 * i + r, last_row);
+    v[i].load(base, (uint32_t)(rr * kD + c * 8));
+  };
   if (k0 < k_end) {
     const int j = min(k0 + lane, k_end - 1);
     load_code<MW>(a.bits, row0 + j, wcur);
     ncur = f16_bits_to_float(a.norms[row0 + j]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) issue_v(i, k0, k_end - 1 - k0);
   }
 
-  for (; k0 < k_end; k0 += kNW * 64) {
-    // ---- issue this block's V loads (rows past the chunk end are clamped; their weight is 0).
-    // 16-bit values: all 16 row passes are in flight while the scores are computed;
-    // fp32 values take twice the registers, so their second half is loaded later.
-    constexpr int IB = T::bytes == 2 ? 16 : 8;
-    vtile<T> v[IB];
+  for (int e = tid; e < GT * M; e += kNW * 64) sq[e] = a.SQ[hq0 * M + e];
+  __syncthreads();
+  build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
+  // build_lut ends with a barrier: nobody reads `nib` any more.
+
+  using PV = typename vecf<GT>::type;
+  float m_run[GT], l_lane[GT];
+  PV acc[8];                                          // acc[e] holds channel 8c+e of all GT heads
 #pragma unroll
-    for (int i = 0; i < IB; ++i) {
-      const int j = min(k0 + 4 * i + r, k_end - 1);
-      v[i].load(a.V, (row0 + j) * kD + c * 8);
-    }
+  for (int g = 0; g < GT; ++g) { m_run[g] = -INFINITY; l_lane[g] = 0.f; }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+
+  for (; k0 < k_end; k0 += kNW * 64) {
     // ---- prefetch the next block's codes and norms
     const int kn = k0 + kNW * 64;
+    const bool have_next = kn < k_end;
     uint32_t wnext[MW];
     float nnext = 0.f;
-    if (kn < k_end) {
+    if (have_next) {
       const int j = min(kn + lane, k_end - 1);
       load_code<MW>(a.bits, row0 + j, wnext);
       nnext = f16_bits_to_float(a.norms[row0 + j]);
@@ -145,62 +153,48 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
       for (int i = 0; i < MW; ++i) wnext[i] = 0u;
     }
     // ---- scores of this block: lane <-> key
-    float s[GT];
-    key_inner<GT, MW>(wcur, lut, s);
+    const PV s = key_inner<GT, MW>(wcur, lut);
     const bool valid = (k0 + lane) < k_end;
-    float alpha[GT], p[GT];
+    PV alpha, p;
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      const float sg = valid ? s[g] * ncur * a.coef2 : -INFINITY;   // log2 domain
+      const float sg = valid ? vget<GT>(s, g) * ncur * a.coef2 : -INFINITY;   // log2 domain
       const float m_new = fmaxf(m_run[g], wave_max(sg));
-      alpha[g] = __builtin_amdgcn_exp2f(m_run[g] - m_new);
-      p[g] = __builtin_amdgcn_exp2f(sg - m_new);
-      l_lane[g] = l_lane[g] * alpha[g] + p[g];
+      const float al = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+      const float pg = __builtin_amdgcn_exp2f(sg - m_new);
+      vset<GT>(alpha, g, al);
+      vset<GT>(p, g, pg);
+      l_lane[g] = l_lane[g] * al + pg;
       m_run[g] = m_new;
     }
     // key (4i + r) of the block goes to slot r*16 + i, so that a V lane reads
     // its 16 weights from consecutive slots
-    {
-      const int slot = (lane & 3) * 16 + (lane >> 2);
-      using PV = typename vecf<GT>::type;
-      PV pv;
-      if constexpr (GT == 1) pv = p[0];
-      else if constexpr (GT == 2) pv = make_float2(p[0], p[1]);
-      else pv = make_float4(p[0], p[1], p[2], p[3]);
-      reinterpret_cast<PV*>(pbuf)[slot] = pv;
-    }
+    reinterpret_cast<PV*>(pbuf)[(lane & 3) * 16 + (lane >> 2)] = p;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // ---- o = o * alpha + sum_j p_j v_j
+    // ---- o = o * alpha + sum_j p_j v_j; each V register is refilled with the
+    // next block's row as soon as it has been consumed.
+    // Straight-line on purpose (no branch on have_next): when there is no next
+    // block every lane re-reads row 0 of the current one, a single cached line.
+    const int kb_next = have_next ? kn : k0;
+    const int lim_next = have_next ? k_end - 1 - kn : 0;
 #pragma unroll
-    for (int g = 0; g < GT; ++g)
+    for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+    const PV* pw = reinterpret_cast<const PV*>(pbuf) + r * 16;
+    PV pv_next = pw[0];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] *= alpha[g];
+    for (int i = 0; i < 16; ++i) {
+      const PV pv = pv_next;
+      if (i + 1 < 16) pv_next = pw[i + 1];            // hide the LDS latency behind this row's FMAs
+      float x[8];
+      v[i].get(x);
 #pragma unroll
-    for (int i0 = 0; i0 < 16; i0 += IB) {
-      if (i0 > 0) {
-#pragma unroll
-        for (int i = 0; i < IB; ++i) {
-          const int j = min(k0 + 4 * (i0 + i) + r, k_end - 1);
-          v[i].load(a.V, (row0 + j) * kD + c * 8);
-        }
-      }
-#pragma unroll
-      for (int i = 0; i < IB; ++i) {
-        float x[8];
-        v[i].get(x);
-        using PV = typename vecf<GT>::type;
-        const PV pv = reinterpret_cast<const PV*>(pbuf)[r * 16 + i0 + i];
-        float pg[GT];
-        if constexpr (GT == 1) { pg[0] = pv; }
-        else if constexpr (GT == 2) { pg[0] = pv.x; pg[1] = pv.y; }
-        else { pg[0] = pv.x; pg[1] = pv.y; pg[2] = pv.z; pg[3] = pv.w; }
-#pragma unroll
-        for (int g = 0; g < GT; ++g)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pg[g], x[e], acc[g][e]);
-      }
+      for (int e = 0; e < 8; ++e) acc[e] += pv * x[e];
+      issue_v(i, kb_next, lim_next);
+      // keep each refill right behind the last use of its registers: hoisting
+      // all sixteen would need a second set of V registers
+      __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -215,17 +209,18 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     const float l = wave_sum(l_lane[g]);
+    float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float x = acc[g][e];
+      float x = vget<GT>(acc[e], g);
       x += __shfl_xor(x, 16);
       x += __shfl_xor(x, 32);
-      acc[g][e] = x;
+      o[e] = x;
     }
     float* rec = merge + (wave * GT + g) * kPartStride;
     if (lane < 16) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = acc[g][e];
+      for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = o[e];
     }
     if (lane == 0) { rec[0] = m_run[g]; rec[1] = l; }
   }
@@ -258,27 +253,62 @@ __global__ void __launch_bounds__(decode_waves(GT, MW * 32) * 64) decode_kernel(
 // Merge the per-chunk records of one query head: out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
 // A kernel of its own: the kernel boundary makes the records of all workgroups
 // visible without device-wide fences inside the streaming kernel.
-__global__ void __launch_bounds__(kD) combine_kernel(const float* __restrict__ part,
-                                                     float* __restrict__ out, int nsplit) {
+// 256 threads: thread (half, ch) sums the chunks s = half, half + 2, ... for
+// channel ch, four independent loads at a time.
+__global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict__ part,
+                                                         float* __restrict__ out, int nsplit) {
+  __shared__ float s_f[512];          // per chunk: 2^(m_s - M)   (nsplit <= 512)
+  __shared__ float s_red[4];
+  __shared__ float s_o[kD], s_l;
   const size_t head = blockIdx.x;
-  const int ch = threadIdx.x;
+  const int tid = threadIdx.x;
   const float* base = part + head * (size_t)nsplit * kPartStride;
-  float mx = -INFINITY;
-  for (int s2 = 0; s2 < nsplit; ++s2) mx = fmaxf(mx, base[(size_t)s2 * kPartStride]);
-  float L = 0.f, O = 0.f;
-  for (int s2 = 0; s2 < nsplit; ++s2) {
-    const float* rec = base + (size_t)s2 * kPartStride;
-    const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
-    L = fmaf(rec[1], f, L);
-    O = fmaf(rec[4 + ch], f, O);
+  // M = max_s m_s
+  float mloc = -INFINITY;
+  for (int s2 = tid; s2 < nsplit; s2 += 2 * kD) mloc = fmaxf(mloc, base[(size_t)s2 * kPartStride]);
+  mloc = wave_max(mloc);
+  if ((tid & 63) == 0) s_red[tid >> 6] = mloc;
+  __syncthreads();
+  const float mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  for (int s2 = tid; s2 < nsplit; s2 += 2 * kD)
+    s_f[s2] = __builtin_amdgcn_exp2f(base[(size_t)s2 * kPartStride] - mx);
+  __syncthreads();
+  const int ch = tid & (kD - 1), half = tid >> 7;
+  float O = 0.f, L = 0.f;
+  int s2 = half;
+  for (; s2 + 6 < nsplit; s2 += 8) {
+    float o[4], l[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* rec = base + (size_t)(s2 + 2 * u) * kPartStride;
+      o[u] = rec[4 + ch];
+      l[u] = rec[1];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float f = s_f[s2 + 2 * u];
+      O = fmaf(o[u], f, O);
+      L = fmaf(l[u], f, L);
+    }
   }
-  out[head * kD + ch] = O / L;
+  for (; s2 < nsplit; s2 += 2) {
+    const float* rec = base + (size_t)s2 * kPartStride;
+    const float f = s_f[s2];
+    O = fmaf(rec[4 + ch], f, O);
+    L = fmaf(rec[1], f, L);
+  }
+  if (half == 1) {
+    s_o[ch] = O;
+    if (ch == 0) s_l = L;
+  }
+  __syncthreads();
+  if (half == 0) out[head * kD + ch] = (O + s_o[ch]) / (L + s_l);
 }
 
 template <typename T, int GT, int MW>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st) {
   static bool attr_set = false;
-  constexpr int kNW = decode_waves(GT, MW * 32);
+  constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   const size_t lds = decode_lds_bytes(GT, MW * 32);
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW>),
@@ -345,7 +375,7 @@ bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
   if (occ > 4) occ = 4;
   const long slots = (long)device_cu_count() * occ;
   long nsplit = (slots + units - 1) / units;
-  const long min_chunk = 64L * decode_waves(gt, sh.m);  // one 64-key block per wave
+  const long min_chunk = 64L * decode_waves(gt, sh.m, sh.dtype == QJL_F32 ? 4 : 2);  // one 64-key block per wave
   long max_split = ((long)sh.n + min_chunk - 1) / min_chunk;
   if (nsplit > max_split) nsplit = max_split;
   if (nsplit > 512) nsplit = 512;
@@ -397,7 +427,7 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
   if (rc == QJL_OK && ev_after) rc = hip_status(hipEventRecord(ev_after, st));
   if (rc != QJL_OK || plan.nsplit == 1) return rc;
   // kernel 3: merge the chunks
-  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(sh.batch * sh.q_heads)), dim3(kD), 0, st,
+  hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(sh.batch * sh.q_heads)), dim3(2 * kD), 0, st,
                      a.part, out, plan.nsplit);
   return launch_status();
 }

@@ -13,10 +13,18 @@
 
 namespace qjl {
 
-template <int GT> struct vecf;
+// GT floats as one value.  Clang vector types (not HIP's float2/float4 structs):
+// arithmetic on the whole vector keeps an LDS access one ds_read_b64/b128; with
+// per-component use the backend would split it into GT 32-bit reads.
+template <int GT> struct vecf { typedef float type __attribute__((ext_vector_type(GT))); };
 template <> struct vecf<1> { using type = float; };
-template <> struct vecf<2> { using type = float2; };
-template <> struct vecf<4> { using type = float4; };
+
+template <int GT> __device__ __forceinline__ float vget(const typename vecf<GT>::type& v, int g) {
+  if constexpr (GT == 1) return v; else return v[g];
+}
+template <int GT> __device__ __forceinline__ void vset(typename vecf<GT>::type& v, int g, float x) {
+  if constexpr (GT == 1) v = x; else v[g] = x;
+}
 
 // LDS floats needed: sq GT*m, 4-bit tables 4*m*GT, byte tables 32*m*GT.
 template <int GT> __host__ __device__ constexpr size_t lut_lds_floats(int m) {
@@ -48,41 +56,25 @@ __device__ __forceinline__ void build_lut(const float* sq, float* nib, float* lu
   const int n_byte = (m >> 3) << 8;
   for (int e = tid; e < n_byte; e += nthreads) {
     const int p = e >> 8, b = e & 255;
-    V lo = nibv[(2 * p) * 16 + (b & 15)];
-    V hi = nibv[(2 * p + 1) * 16 + (b >> 4)];
-    V r;
-    if constexpr (GT == 1) { r = lo + hi; }
-    else if constexpr (GT == 2) { r = make_float2(lo.x + hi.x, lo.y + hi.y); }
-    else { r = make_float4(lo.x + hi.x, lo.y + hi.y, lo.z + hi.z, lo.w + hi.w); }
-    lutv[e] = r;
+    lutv[e] = nibv[(2 * p) * 16 + (b & 15)] + nibv[(2 * p + 1) * 16 + (b >> 4)];
   }
   __syncthreads();
 }
 
 // <S q_g, signs of one key> for g < GT, from the key's MW code words.
 template <int GT, int MW>
-__device__ __forceinline__ void key_inner(const uint32_t (&w)[MW], const float* lut,
-                                          float (&out)[GT]) {
+__device__ __forceinline__ typename vecf<GT>::type key_inner(const uint32_t (&w)[MW], const float* lut) {
   using V = typename vecf<GT>::type;
   const V* lutv = reinterpret_cast<const V*>(lut);
-  float a0[GT], a1[GT];
-#pragma unroll
-  for (int g = 0; g < GT; ++g) { a0[g] = 0.f; a1[g] = 0.f; }
+  V a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;         // four chains: adds do not wait on each other
 #pragma unroll
   for (int wi = 0; wi < MW; ++wi) {
-#pragma unroll
-    for (int by = 0; by < 4; ++by) {
-      const int p = wi * 4 + by;
-      const uint32_t b = (w[wi] >> (8 * by)) & 255u;
-      V e = lutv[p * 256 + b];
-      float* a = (by & 1) ? a1 : a0;
-      if constexpr (GT == 1) { a[0] += e; }
-      else if constexpr (GT == 2) { a[0] += e.x; a[1] += e.y; }
-      else { a[0] += e.x; a[1] += e.y; a[2] += e.z; a[3] += e.w; }
-    }
+    a0 += lutv[(wi * 4 + 0) * 256 + (w[wi] & 255u)];
+    a1 += lutv[(wi * 4 + 1) * 256 + ((w[wi] >> 8) & 255u)];
+    a2 += lutv[(wi * 4 + 2) * 256 + ((w[wi] >> 16) & 255u)];
+    a3 += lutv[(wi * 4 + 3) * 256 + (w[wi] >> 24)];
   }
-#pragma unroll
-  for (int g = 0; g < GT; ++g) out[g] = a0[g] + a1[g];
+  return (a0 + a1) + (a2 + a3);
 }
 
 // Load the MW code words of one key (row `row` of bits[*, MW*4 bytes]).

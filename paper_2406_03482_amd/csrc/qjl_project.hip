@@ -17,18 +17,27 @@ project128_kernel(const void* __restrict__ Q, const void* __restrict__ S, float*
 
   const int c = tid & 15;                     // 8-element slice of the row
   const int r = tid >> 4;                     // 0..15: row inside a pass of 16 rows
+  // sixteen rows of S per pass; the loads of kPasses passes are issued together so
+  // that their latencies overlap (S sits in L2 after the first workgroups)
+  constexpr int kPasses = 8;
   float q[8];
   load8<T>(Q, (size_t)row * 128 + c * 8, q);
-  for (int i0 = 0; i0 < m; i0 += 16) {
-    int i = i0 + r;
-    int ic = i < m ? i : m - 1;               // clamp: never read past S
-    float s[8];
-    load8<T>(S, (size_t)ic * 128 + c * 8, s);
-    float acc = 0.f;
+  for (int i0 = 0; i0 < m; i0 += 16 * kPasses) {
+    float s[kPasses][8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) acc = fmaf(s[t], q[t], acc);
-    acc = row16_sum(acc);
-    if (c == 0 && i < m) SQ[(size_t)row * m + i] = acc;
+    for (int u = 0; u < kPasses; ++u) {
+      const int i = min(i0 + 16 * u + r, m - 1);          // clamp: never read past S
+      load8<T>(S, (size_t)i * 128 + c * 8, s[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kPasses; ++u) {
+      float acc = 0.f;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc = fmaf(s[u][t], q[t], acc);
+      acc = row16_sum(acc);
+      const int i = i0 + 16 * u + r;
+      if (c == 0 && i < m) SQ[(size_t)row * m + i] = acc;
+    }
   }
 }
 

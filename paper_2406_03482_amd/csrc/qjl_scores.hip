@@ -47,10 +47,9 @@ __global__ void __launch_bounds__(256) scores_kernel(scores_args a) {
     uint32_t w[MW];
     load_code<MW>(a.bits, row0 + j, w);
     const float nu = f16_bits_to_float(a.norms[row0 + j]);
-    float s[GT];
-    key_inner<GT, MW>(w, lut, s);
+    const typename vecf<GT>::type s = key_inner<GT, MW>(w, lut);
 #pragma unroll
-    for (int g = 0; g < GT; ++g) a.out[(hq0 + g) * a.n + j] = a.coef * nu * s[g];
+    for (int g = 0; g < GT; ++g) a.out[(hq0 + g) * a.n + j] = a.coef * nu * vget<GT>(s, g);
   }
 }
 
