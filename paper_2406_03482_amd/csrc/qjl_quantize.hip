@@ -32,21 +32,43 @@ template <> struct mma<f16_t> {
   }
 };
 
-constexpr int kTok = 32;        // keys per tile = N of the 32x32 MFMA tile
+constexpr int kTok = 64;        // keys per tile: two N = 32 MFMA sub-tiles
 constexpr int kRowU4 = 17;      // LDS row pitch in 16-byte units: 256 B of key + 16 B pad
 
-// Sixteen accumulators of one lane -> 16 bits, bit v = [acc[v] >= 0].
-// v_alignbit shifts the IEEE sign bit of each accumulator in; a sum that
-// starts from +0 can only be -0 if it is within rounding of zero.
-__device__ __forceinline__ uint32_t nonneg_bits16(const f32x16_t& acc) {
-  uint32_t t = 0;
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+// sum of squares of the eight 16-bit elements of one 16-byte chunk, fp32 accumulation
+// (v_dot2_f32_bf16 / v_dot2_f32_f16: two products and the add per instruction)
+template <typename T> __device__ __forceinline__ float sumsq8(const uint4& u);
+template <> __device__ __forceinline__ float sumsq8<bf16_t>(const uint4& u) {
+  bf16x2_t p[4];
+  __builtin_memcpy(p, &u, 16);
+  float s = 0.f;
 #pragma unroll
-  for (int v = 15; v >= 0; --v) t = __builtin_amdgcn_alignbit(t, __float_as_uint(acc[v]), 31);
-  return (~t) & 0xFFFFu;
+  for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2_f32_bf16(p[i], p[i], s, false);
+  return s;
 }
+template <> __device__ __forceinline__ float sumsq8<f16_t>(const uint4& u) {
+  f16x2_t p[4];
+  __builtin_memcpy(p, &u, 16);
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2(p[i], p[i], s, false);
+  return s;
+}
+
+// Sign extraction: v_alignbit(t, acc, 31) shifts the IEEE sign bit of an accumulator
+// into t; sixteen of them (v = 15..0) give bit v = sign of acc[v], and the code
+// bit is its complement ([acc >= 0]).  A sum that starts from +0 can only be -0
+// if it is within rounding of zero.
 
 // PPW = projections per wave (32, 64 or 128); a workgroup of four waves covers
 // 4*PPW projections, blockIdx.y selects which block of 4*PPW out of m.
+// Per iteration a workgroup turns one tile of 64 keys into 64 code rows:
+//   HBM -> registers (issued one tile ahead) -> norm + LDS (padded rows)
+//   LDS -> MFMA B operands, S from registers, accumulators -> bits in registers
+//   bits -> LDS -> HBM as whole rows (16 bytes per lane, contiguous)
 template <typename T, int PPW>
 __global__ void __launch_bounds__(256, 2)
 quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S,
@@ -55,15 +77,15 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   using frag = typename mma<T>::frag;
   constexpr int NA = PPW / 32;            // 32x32 MFMA tiles per wave along the projections
   constexpr int WPT = 4 * PPW / 32;       // code words per key written by this workgroup
-  constexpr int OPITCH = WPT + 1;         // odd pitch: conflict-free LDS writes
   __shared__ uint4 kbuf[2][kTok * kRowU4];
-  __shared__ uint32_t obuf[2][kTok * OPITCH];
+  __shared__ uint4 obuf[2][kTok * WPT / 4];
+  __shared__ float nsq[2][kTok];           // squared norms of the tile's keys
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;                // which 8 of the 16 k of an MFMA step this lane feeds
-  const int j = lane & 31;                // A: row of the S tile, B/D: key of the tile
+  const int j = lane & 31;                // A: row of the S tile, B/D: key of the sub-tile
   const int proj_base = blockIdx.y * (4 * PPW) + wave * PPW;
   const int words_per_row = m >> 5;
 
@@ -84,38 +106,48 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     }
   }
 
-  // ---- loader: thread -> (row lrow + 16u, 16-byte column lcol) of a tile
+  // ---- loader: thread -> (row lrow + 16u, 16-byte column lcol) of a tile, u = 0..3
   const int lrow = tid >> 4, lcol = tid & 15;
-  uint4 pre[2];
+  uint4 pre[4];
   auto load_tile = [&](int tile) {
+    const long row0 = (long)tile * kTok;
+    if (row0 + kTok <= rows) {            // uniform: whole tile inside K
+      const uint16_t* kp = K + ((size_t)row0 + lrow) * 128 + lcol * 8;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      long row = (long)tile * kTok + lrow + 16 * u;
-      if (row >= rows) row = rows - 1;    // clamp: stay inside K, results of such rows are dropped
-      pre[u] = *reinterpret_cast<const uint4*>(K + (size_t)row * 128 + lcol * 8);
+      for (int u = 0; u < 4; ++u) pre[u] = *reinterpret_cast<const uint4*>(kp + u * 16 * 128);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        long row = row0 + lrow + 16 * u;
+        if (row >= rows) row = rows - 1;  // clamp: stay inside K, results of such rows are dropped
+        pre[u] = *reinterpret_cast<const uint4*>(K + (size_t)row * 128 + lcol * 8);
+      }
     }
   };
-  auto stage_tile = [&](int tile, int buf) {
+  auto stage_tile = [&](int buf) {
+    float ss[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
       kbuf[buf][(lrow + 16 * u) * kRowU4 + lcol] = pre[u];
-      float x[8];
-      unpack2<T>(pre[u].x, x[0], x[1]); unpack2<T>(pre[u].y, x[2], x[3]);
-      unpack2<T>(pre[u].z, x[4], x[5]); unpack2<T>(pre[u].w, x[6], x[7]);
-      float ss = 0.f;
+      ss[u] = sumsq8<T>(pre[u]);
+    }
 #pragma unroll
-      for (int t = 0; t < 8; ++t) ss = fmaf(x[t], x[t], ss);
-      ss = row16_sum(ss);                 // the 16 lanes of a DPP row hold one key
-      const long row = (long)tile * kTok + lrow + 16 * u;
-      if (lcol == 0 && blockIdx.y == 0 && row < rows) norms[row] = float_to_f16_bits(sqrtf(ss));
+    for (int u = 0; u < 4; ++u) ss[u] = row16_sum(ss[u]);   // the 16 lanes of a DPP row hold one key
+    if (lcol == 0) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) nsq[buf][lrow + 16 * u] = ss[u];
     }
   };
 
   int tile = blockIdx.x;
   if (tile < num_tiles) {
     load_tile(tile);
-    stage_tile(tile, 0);
+    stage_tile(0);
   }
+  // All loads issued so far (the S fragments above all) must have landed before
+  // the loop: otherwise the loop body carries waits for them that would also
+  // wait for each iteration's prefetch of the next tile.
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   int buf = 0;
@@ -124,51 +156,107 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     const bool has_next = next < num_tiles;
     if (has_next) load_tile(next);
 
-    // B operands: key j, k in [16s + 8h, 16s + 8h + 8)
-    frag bfrag[8];
+    // ---- MFMA phase.  The tile's work is cut into NU units of two accumulator
+    // chains (8 MFMAs each).  While unit u accumulates, the sign bits of unit
+    // u-1 are extracted (v_alignbit) in the shadow of its MFMAs, and the B
+    // operand of step g+2 is fetched from LDS, so the matrix pipe never waits
+    // for the vector ALU or for LDS.  sched_barrier keeps that interleaving.
+    constexpr int NU = NA >= 2 ? NA : 1;
+    auto sub_of = [](int u, int c) { return NA >= 2 ? u / (NA / 2) : c; };
+    auto a_of = [](int u, int c) { return NA >= 2 ? 2 * (u % (NA / 2)) + c : 0; };
+    auto lds_b = [&](int sub, int s) {          // key sub*32 + j, k in [16s + 8h, 16s + 8h + 8)
+      frag f;
+      const uint4 u4 = kbuf[buf][(sub * 32 + j) * kRowU4 + 2 * s + h];
+      __builtin_memcpy(&f, &u4, 16);
+      return f;
+    };
+    constexpr int kSteps = NU * 8;
+    frag bq[3][2];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      uint4 u = kbuf[buf][j * kRowU4 + 2 * s + h];
-      __builtin_memcpy(&bfrag[s], &u, 16);
+    for (int g = 0; g < 2; ++g) {
+      bq[g][0] = lds_b(sub_of(g / 8, 0), g % 8);
+      if constexpr (NA == 1) bq[g][1] = lds_b(1, g % 8);
     }
-    uint32_t half[NA];
-    if constexpr (NA >= 2) {
+    f32x16_t acc[2][2];
+    uint32_t tb[2] = {0u, 0u};
+    uint32_t half[2 * NU];
 #pragma unroll
-      for (int a = 0; a < NA; a += 2) {
-        f32x16_t acc0 = {0}, acc1 = {0};
+    for (int u = 0; u <= NU; ++u) {             // round NU only drains the last unit's bits
+      const int par = u & 1;
+      if (u < NU) {
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-          acc0 = mma<T>::run(sfrag[a][s], bfrag[s], acc0);
-          acc1 = mma<T>::run(sfrag[a + 1][s], bfrag[s], acc1);
-        }
-        half[a] = nonneg_bits16(acc0);
-        half[a + 1] = nonneg_bits16(acc1);
+        for (int v = 0; v < 16; ++v) { acc[par][0][v] = 0.f; acc[par][1][v] = 0.f; }
       }
-    } else {
-      f32x16_t acc0 = {0};
 #pragma unroll
-      for (int s = 0; s < 8; ++s) acc0 = mma<T>::run(sfrag[0][s], bfrag[s], acc0);
-      half[0] = nonneg_bits16(acc0);
+      for (int s = 0; s < 8; ++s) {
+        const int g = u * 8 + s;
+        if (g + 2 < kSteps) {
+          bq[(g + 2) % 3][0] = lds_b(sub_of((g + 2) / 8, 0), (g + 2) % 8);
+          if constexpr (NA == 1) bq[(g + 2) % 3][1] = lds_b(1, (g + 2) % 8);
+        }
+        if (u < NU) {
+          acc[par][0] = mma<T>::run(sfrag[a_of(u, 0)][s], bq[g % 3][0], acc[par][0]);
+          acc[par][1] = mma<T>::run(sfrag[a_of(u, 1)][s], bq[g % 3][NA == 1 ? 1 : 0], acc[par][1]);
+        }
+        if (u > 0) {
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            tb[c] = __builtin_amdgcn_alignbit(tb[c], __float_as_uint(acc[par ^ 1][c][15 - 2 * s]), 31);
+            tb[c] = __builtin_amdgcn_alignbit(tb[c], __float_as_uint(acc[par ^ 1][c][14 - 2 * s]), 31);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (u > 0) {                              // bit v = [acc[v] >= 0]
+        half[2 * (u - 1)] = (~tb[0]) & 0xFFFFu;
+        half[2 * (u - 1) + 1] = (~tb[1]) & 0xFFFFu;
+        tb[0] = 0u;
+        tb[1] = 0u;
+      }
     }
-    // lane (h, j) holds PPW/2 consecutive code bits of key j, starting at bit
-    // wave*PPW + h*PPW/2 of this workgroup's 4*PPW
-    if constexpr (NA >= 2) {
+    // lane (h, j) holds PPW/2 consecutive code bits of keys j and 32 + j, starting
+    // at bit wave*PPW + h*PPW/2 of this workgroup's 4*PPW
 #pragma unroll
-      for (int a = 0; a < NA; a += 2)
-        obuf[buf][j * OPITCH + wave * (PPW / 32) + h * (PPW / 64) + a / 2] = half[a] | (half[a + 1] << 16);
-    } else {
-      reinterpret_cast<uint16_t*>(obuf[buf])[(j * OPITCH + wave) * 2 + h] = (uint16_t)half[0];
+    for (int sub = 0; sub < 2; ++sub) {
+      uint32_t* orow = reinterpret_cast<uint32_t*>(obuf[buf]) + (sub * 32 + j) * WPT;
+      if constexpr (NA == 4) {
+        *reinterpret_cast<uint2*>(orow + wave * 4 + h * 2) =
+            make_uint2(half[4 * sub] | (half[4 * sub + 1] << 16), half[4 * sub + 2] | (half[4 * sub + 3] << 16));
+      } else if constexpr (NA == 2) {
+        orow[wave * 2 + h] = half[2 * sub] | (half[2 * sub + 1] << 16);
+      } else {
+        reinterpret_cast<uint16_t*>(orow)[wave * 2 + h] = (uint16_t)half[sub];
+      }
     }
 
-    if (has_next) stage_tile(next, buf ^ 1);
+    if (has_next) stage_tile(buf ^ 1);
     __syncthreads();
 
-    // coalesced copy of the tile's code words to HBM
-    for (int idx = tid; idx < kTok * WPT; idx += 256) {
-      const int tok = idx / WPT, wd = idx - tok * WPT;
+    // whole code rows and the tile's norms go to HBM, 16 contiguous bytes per lane
+    constexpr int kChunksPerRow = WPT / 4;
+    if (tid < kTok * kChunksPerRow) {
+      const int tok = tid / kChunksPerRow, part = tid % kChunksPerRow;
       const long row = (long)tile * kTok + tok;
       if (row < rows)
-        bits[(size_t)row * words_per_row + blockIdx.y * WPT + wd] = obuf[buf][tok * OPITCH + wd];
+        *reinterpret_cast<uint4*>(bits + (size_t)row * words_per_row + blockIdx.y * WPT + part * 4) =
+            obuf[buf][tid];
+    }
+    if (blockIdx.y == 0 && tid >= 248) {              // 8 lanes x 8 norms
+      const int q = tid - 248;
+      const long row = (long)tile * kTok + q * 8;
+      uint32_t pk[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t lo = float_to_f16_bits(sqrtf(nsq[buf][q * 8 + 2 * t]));
+        const uint32_t hi = float_to_f16_bits(sqrtf(nsq[buf][q * 8 + 2 * t + 1]));
+        pk[t] = lo | (hi << 16);
+      }
+      if (row + 8 <= rows) {
+        *reinterpret_cast<uint4*>(norms + row) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+      } else {
+        for (int t = 0; t < 8; ++t)
+          if (row + t < rows) norms[row + t] = (uint16_t)(pk[t >> 1] >> (16 * (t & 1)));
+      }
     }
   }
 }
