@@ -236,7 +236,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
-                    "metric is quoted on), c3, c5a, c5b (decode) or c4 (prefill quantize); for profiling single kernels")
+                    "metric is quoted on), c3, c5a, c5b (decode) or c4 (prefill quantize), for profiling single kernels; "
+                    "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -255,6 +256,17 @@ def main() -> int:
     dev = "cuda:0"
     ev = HipEvents()
 
+    if args.workload == "copy":
+        # calibration aid for the HBM counters: a plain device copy of known size
+        # (1 GiB read + 1 GiB written per launch), nothing of the method
+        src = torch.ones((1 << 29,), dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(max(1, args.steps)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": "copy", "bytes_read_per_launch": src.numel() * 2,
+                          "bytes_written_per_launch": src.numel() * 2, "launches": max(1, args.steps)}))
+        return 0
     names = {k.split("_")[0]: k for k in inputs.WORKLOADS}
     if args.workload not in names or args.workload == "c1":
         print(f"bench.py: unknown workload {args.workload!r}", file=sys.stderr)

@@ -132,9 +132,11 @@ int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S,
 /*
  * qjl_decode_attention, plus kernel timing without a profiler: the two
  * caller-owned events (hipEvent_t passed as void*, created with timing
- * enabled; either may be NULL) are recorded on `stream` immediately before
- * and immediately after the attention kernel (Algorithm 1 EstimateScores +
- * Eq. (1)), i.e. after the small query-projection kernel has been enqueued.
+ * enabled; either may be NULL) receive the start and the stop timestamp of
+ * the attention kernel itself (Algorithm 1 EstimateScores + Eq. (1)), the
+ * way a profiler sees that dispatch; the small query-projection kernel
+ * before it and the chunk-merge kernel after it are outside the interval.
+ * hipEventElapsedTime(before, after) is valid once `after` has completed.
  * Everything else is exactly qjl_decode_attention.
  */
 int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void* S,

@@ -10,6 +10,7 @@
 #include "qjl_common.hpp"
 #include "qjl_lut.hpp"
 
+#include <hip/hip_ext.h>
 #include <stdlib.h>
 
 namespace qjl {
@@ -306,7 +307,8 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
 }
 
 template <typename T, int GT, int MW>
-int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st) {
+int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
+             hipEvent_t ev0, hipEvent_t ev1) {
   static bool attr_set = false;
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   const size_t lds = decode_lds_bytes(GT, MW * 32);
@@ -319,25 +321,31 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
   const long units = (long)sh.batch * sh.kv_heads * a.groups_per_kv;
   const long total = units * plan.nsplit;
   if (total > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64), lds, st, a);
+  if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64),
+                          (uint32_t)lds, st, ev0, ev1, 0u, a);
+  else
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
 template <typename T, int MW>
-int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st) {
+int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
+             hipEvent_t ev0, hipEvent_t ev1) {
   switch (plan.gt) {
-    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW>(sh, plan, a, st); else return QJL_ERR_UNSUPPORTED;
-    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW>(sh, plan, a, st); else return QJL_ERR_UNSUPPORTED;
-    default: return launch_t<T, 1, MW>(sh, plan, a, st);
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW>(sh, plan, a, st, ev0, ev1);
   }
 }
 
 template <typename T>
-int launch_m(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st) {
+int launch_m(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
+             hipEvent_t ev0, hipEvent_t ev1) {
   switch (sh.m) {
-    case 128: return launch_g<T, 4>(sh, plan, a, st);
-    case 256: return launch_g<T, 8>(sh, plan, a, st);
-    case 512: return launch_g<T, 16>(sh, plan, a, st);
+    case 128: return launch_g<T, 4>(sh, plan, a, st, ev0, ev1);
+    case 256: return launch_g<T, 8>(sh, plan, a, st, ev0, ev1);
+    case 512: return launch_g<T, 16>(sh, plan, a, st, ev0, ev1);
     default: return QJL_ERR_UNSUPPORTED;
   }
 }
@@ -415,16 +423,11 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
-  if (ev_before) {
-    hipError_t e = hipEventRecord(ev_before, st);
-    if (e != hipSuccess) return hip_status(e);
-  }
   switch (sh.dtype) {
-    case QJL_F32: rc = launch_m<f32_t>(sh, plan, a, st); break;
-    case QJL_F16: rc = launch_m<f16_t>(sh, plan, a, st); break;
-    default: rc = launch_m<bf16_t>(sh, plan, a, st); break;
+    case QJL_F32: rc = launch_m<f32_t>(sh, plan, a, st, ev_before, ev_after); break;
+    case QJL_F16: rc = launch_m<f16_t>(sh, plan, a, st, ev_before, ev_after); break;
+    default: rc = launch_m<bf16_t>(sh, plan, a, st, ev_before, ev_after); break;
   }
-  if (rc == QJL_OK && ev_after) rc = hip_status(hipEventRecord(ev_after, st));
   if (rc != QJL_OK || plan.nsplit == 1) return rc;
   // kernel 3: merge the chunks
   hipLaunchKernelGGL(combine_kernel, dim3((unsigned)(sh.batch * sh.q_heads)), dim3(2 * kD), 0, st,
