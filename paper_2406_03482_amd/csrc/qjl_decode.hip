@@ -110,20 +110,23 @@ decode_kernel(decode_args a) {
   int k0 = k_begin + wave * 64;
   uint32_t wcur[MW];
   float ncur = 0.f;
-  vtile<T> v[16];
+  // V rows in flight per lane: 16 (a whole 64-key block ahead), or 8 where the
+  // four-head group needs the registers for its accumulators and tables
+  constexpr int VD = GT == 4 ? 8 : 16;
+  vtile<T> v[VD];
   // row (4i + r) of the block starting at key kb: uniform base pointer + a
   // 32-bit lane offset, the row clamped to the last key of the chunk
-  auto issue_v = [&](int i, int kb, int last_row) {
+  auto issue_v = [&](int slot, int i, int kb, int last_row) {   // row pass i of block kb -> v[slot]
     const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * T::bytes);
     const int rr = min(4 * i + r, last_row);
-    v[i].load(base, (uint32_t)(rr * kD + c * 8));
+    v[slot].load(base, (uint32_t)(rr * kD + c * 8));
   };
   if (k0 < k_end) {
     const int j = min(k0 + lane, k_end - 1);
     load_code<MW>(a.bits, row0 + j, wcur);
     ncur = f16_bits_to_float(a.norms[row0 + j]);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) issue_v(i, k0, k_end - 1 - k0);
+    for (int i = 0; i < VD; ++i) issue_v(i, i, k0, k_end - 1 - k0);
   }
 
   for (int e = tid; e < GT * M; e += kNW * 64) sq[e] = a.SQ[hq0 * M + e];
@@ -140,26 +143,23 @@ decode_kernel(decode_args a) {
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
   for (; k0 < k_end; k0 += kNW * 64) {
-    // ---- prefetch the next block's codes and norms
     const int kn = k0 + kNW * 64;
     const bool have_next = kn < k_end;
-    uint32_t wnext[MW];
-    float nnext = 0.f;
-    if (have_next) {
-      const int j = min(kn + lane, k_end - 1);
-      load_code<MW>(a.bits, row0 + j, wnext);
-      nnext = f16_bits_to_float(a.norms[row0 + j]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < MW; ++i) wnext[i] = 0u;
-    }
     // ---- scores of this block: lane <-> key
     const PV s = key_inner<GT, MW>(wcur, lut);
     const bool valid = (k0 + lane) < k_end;
+    const float nu = ncur;
+    // the code registers are free again: fetch the next block's codes and norm
+    // into them now, the value pass below hides the latency
+    if (have_next) {
+      const int j = min(kn + lane, k_end - 1);
+      load_code<MW>(a.bits, row0 + j, wcur);
+      ncur = f16_bits_to_float(a.norms[row0 + j]);
+    }
     PV alpha, p;
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      const float sg = valid ? vget<GT>(s, g) * ncur * a.coef2 : -INFINITY;   // log2 domain
+      const float sg = valid ? vget<GT>(s, g) * nu * a.coef2 : -INFINITY;   // log2 domain
       const float m_new = fmaxf(m_run[g], wave_max(sg));
       const float al = __builtin_amdgcn_exp2f(m_run[g] - m_new);
       const float pg = __builtin_amdgcn_exp2f(sg - m_new);
@@ -189,10 +189,11 @@ decode_kernel(decode_args a) {
       const PV pv = pv_next;
       if (i + 1 < 16) pv_next = pw[i + 1];            // hide the LDS latency behind this row's FMAs
       float x[8];
-      v[i].get(x);
+      v[i % VD].get(x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += pv * x[e];
-      issue_v(i, kb_next, lim_next);
+      if (i + VD < 16) issue_v(i % VD, i + VD, k0, k_end - 1 - k0);   // later row of this block
+      else issue_v(i % VD, i + VD - 16, kb_next, lim_next);          // first rows of the next block
       // keep each refill right behind the last use of its registers: hoisting
       // all sixteen would need a second set of V registers
       __builtin_amdgcn_sched_barrier(0);
@@ -200,9 +201,6 @@ decode_kernel(decode_args a) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-    for (int i = 0; i < MW; ++i) wcur[i] = wnext[i];
-    ncur = nnext;
   }
 
   __syncthreads();   // every wave is done with the tables: their space now takes the merge records
