@@ -253,55 +253,49 @@ decode_kernel(decode_args a) {
 // A kernel of its own: the kernel boundary makes the records of all workgroups
 // visible without device-wide fences inside the streaming kernel.
 // 256 threads: thread (half, ch) sums the chunks s = half, half + 2, ... for
-// channel ch, four independent loads at a time.
+// channel ch.  Every load of a pass is issued before the first use, so a head
+// with up to 16 chunks costs a single round trip to memory.
 __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict__ part,
                                                          float* __restrict__ out, int nsplit) {
-  __shared__ float s_f[512];          // per chunk: 2^(m_s - M)   (nsplit <= 512)
-  __shared__ float s_red[4];
-  __shared__ float s_o[kD], s_l;
+  __shared__ float s_m[512], s_l[512];   // per chunk: running max and sum (nsplit <= 512)
+  __shared__ float s_o[kD], s_lsum;
   const size_t head = blockIdx.x;
   const int tid = threadIdx.x;
   const float* base = part + head * (size_t)nsplit * kPartStride;
-  // M = max_s m_s
-  float mloc = -INFINITY;
-  for (int s2 = tid; s2 < nsplit; s2 += 2 * kD) mloc = fmaxf(mloc, base[(size_t)s2 * kPartStride]);
-  mloc = wave_max(mloc);
-  if ((tid & 63) == 0) s_red[tid >> 6] = mloc;
-  __syncthreads();
-  const float mx = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-  for (int s2 = tid; s2 < nsplit; s2 += 2 * kD)
-    s_f[s2] = __builtin_amdgcn_exp2f(base[(size_t)s2 * kPartStride] - mx);
-  __syncthreads();
   const int ch = tid & (kD - 1), half = tid >> 7;
-  float O = 0.f, L = 0.f;
-  int s2 = half;
-  for (; s2 + 6 < nsplit; s2 += 8) {
-    float o[4], l[4];
+  constexpr int kB = 8;                  // chunks per thread and pass
+  float O = 0.f, L = 0.f, mx = -INFINITY;
+  for (int s0 = 0; s0 < nsplit; s0 += 2 * kB) {
+    float o[kB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float* rec = base + (size_t)(s2 + 2 * u) * kPartStride;
-      o[u] = rec[4 + ch];
-      l[u] = rec[1];
+    for (int u = 0; u < kB; ++u) {
+      const int s2 = s0 + half + 2 * u;
+      o[u] = s2 < nsplit ? base[(size_t)s2 * kPartStride + 4 + ch] : 0.f;
+    }
+    if (s0 == 0) {                       // first pass also fetches every chunk's (max, sum)
+      for (int s2 = tid; s2 < nsplit; s2 += 2 * kD) {
+        s_m[s2] = base[(size_t)s2 * kPartStride];
+        s_l[s2] = base[(size_t)s2 * kPartStride + 1];
+      }
+      __syncthreads();
+      for (int s2 = 0; s2 < nsplit; ++s2) mx = fmaxf(mx, s_m[s2]);
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const float f = s_f[s2 + 2 * u];
-      O = fmaf(o[u], f, O);
-      L = fmaf(l[u], f, L);
+    for (int u = 0; u < kB; ++u) {
+      const int s2 = s0 + half + 2 * u;
+      if (s2 < nsplit) {
+        const float f = __builtin_amdgcn_exp2f(s_m[s2] - mx);
+        O = fmaf(o[u], f, O);
+        L = fmaf(s_l[s2], f, L);
+      }
     }
-  }
-  for (; s2 < nsplit; s2 += 2) {
-    const float* rec = base + (size_t)s2 * kPartStride;
-    const float f = s_f[s2];
-    O = fmaf(rec[4 + ch], f, O);
-    L = fmaf(rec[1], f, L);
   }
   if (half == 1) {
     s_o[ch] = O;
-    if (ch == 0) s_l = L;
+    if (ch == 0) s_lsum = L;
   }
   __syncthreads();
-  if (half == 0) out[head * kD + ch] = (O + s_o[ch]) / (L + s_l);
+  if (half == 0) out[head * kD + ch] = (O + s_o[ch]) / (L + s_lsum);
 }
 
 template <typename T, int GT, int MW>
