@@ -54,9 +54,21 @@ __device__ __forceinline__ void build_lut(const float* sq, float* nib, float* lu
   const V* nibv = reinterpret_cast<const V*>(nib);
   V* lutv = reinterpret_cast<V*>(lut);
   const int n_byte = (m >> 3) << 8;
-  for (int e = tid; e < n_byte; e += nthreads) {
-    const int p = e >> 8, b = e & 255;
-    lutv[e] = nibv[(2 * p) * 16 + (b & 15)] + nibv[(2 * p + 1) * 16 + (b >> 4)];
+  if constexpr (GT == 1) {
+    // four consecutive byte values share the high nibble: one 16-byte read of the
+    // low table, one broadcast read of the high table, one 16-byte write
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4* nib4 = reinterpret_cast<const f4*>(nib);
+    f4* lut4 = reinterpret_cast<f4*>(lut);
+    for (int e4 = tid; e4 < (n_byte >> 2); e4 += nthreads) {
+      const int p = e4 >> 6, b0 = (e4 & 63) << 2;
+      lut4[e4] = nib4[(2 * p) * 4 + ((b0 & 15) >> 2)] + nib[(2 * p + 1) * 16 + (b0 >> 4)];
+    }
+  } else {
+    for (int e = tid; e < n_byte; e += nthreads) {
+      const int p = e >> 8, b = e & 255;
+      lutv[e] = nibv[(2 * p) * 16 + (b & 15)] + nibv[(2 * p + 1) * 16 + (b >> 4)];
+    }
   }
   __syncthreads();
 }
