@@ -374,3 +374,64 @@ def _popcount8(t: torch.Tensor) -> torch.Tensor:
     if _POP is None:
         _POP = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device=DEV)
     return _POP[t.long()]
+
+
+# ------------------------------------------------------------------ streams and graphs
+def test_decode_on_side_stream_and_in_a_graph():
+    """The calls enqueue on the caller's stream only, so a decode step can be
+    captured in a HIP graph: every replay (with other eager work and
+    synchronisations in between, and new queries written into the captured
+    buffers) must equal the eager result for the same inputs."""
+    say("[graph] decode step captured and replayed")
+    B, Hq, Hkv, n, d, m, scale = 1, 8, 2, 3000, 128, 256, 0.0884
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 71, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 73, DEV)
+    S = qjl.qjl_make_sketch(13, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    Qs = [inputs.make_normal((B, Hq, d), torch.bfloat16, 80 + i, DEV) for i in range(4)]
+    Q = Qs[0].clone()
+    ws = torch.empty((qjl.qjl_decode_workspace_bytes(B, Hq, Hkv, n, d, m),), dtype=torch.uint8, device=DEV)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # eager on a non-default stream
+        qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, out=out, workspace=ws)
+    side.synchronize()
+    ref0 = orc.decode_attention(inputs.to_f64(Q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), scale)
+    assert_attention(out.cpu().numpy(), ref0)
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, out=out, workspace=ws)
+    for i, q in enumerate(Qs):
+        Q.copy_(q)                                     # eager work between replays
+        out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = out.clone()
+        eager = qjl.qjl_decode_attention(q, S, bits_d, nu_d, V, scale)
+        assert torch.equal(got, eager), f"replay {i} differs from the eager result"
+        ref = orc.decode_attention(inputs.to_f64(q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), scale)
+        assert_attention(got.cpu().numpy(), ref)
+
+
+def test_many_small_units():
+    """Many (batch, head) units with a short context: one workgroup per unit, no chunking."""
+    say("[decode] B=24 Hq=16 Hkv=16 n=200")
+    B, Hq, Hkv, n, d, m, scale = 24, 16, 16, 200, 128, 256, 0.0884
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 91, DEV)
+    Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 92, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 93, DEV)
+    S = qjl.qjl_make_sketch(15, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    ref = orc.decode_attention(inputs.to_f64(Q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), scale)
+    out = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale)
+    assert_attention(out.cpu().numpy(), ref)
+    sc = qjl.qjl_scores(qjl.qjl_project_query(Q, S), bits_d, nu_d, scale).cpu().numpy()
+    SQ32 = orc.project_query(inputs.to_f64(Q), inputs.to_f64(S)).astype(np.float32).astype(np.float64)
+    # the GPU's own S q differs from the oracle's by fp32 rounding only: compare the scores loosely here,
+    # the strict comparison (same S q on both sides) is test_scores_parity
+    ref_sc = orc.estimate_scores(SQ32, bits, nu16, scale)
+    rms = np.sqrt(np.mean(ref_sc ** 2, axis=-1, keepdims=True))
+    assert np.all(np.abs(sc - ref_sc) <= 2e-3 * np.maximum(np.abs(ref_sc), 1e-2 * rms))
