@@ -137,8 +137,7 @@ struct decode_plan {
   int gt;            // query heads handled together by one workgroup (divides G)
   int nsplit;        // context chunks per (batch, kv head, head group)
   int chunk;         // keys per chunk (multiple of 64)
-  size_t off_sq;     // byte offsets inside the workspace
-  size_t off_part;
+  size_t off_part;   // byte offset of the per-chunk records inside the workspace
   size_t total;      // bytes
 };
 bool plan_decode(const qjl_shape& sh, decode_plan* plan);

@@ -4,9 +4,12 @@
 //
 // HBM-bound: per key and KV head the kernel reads m/8 code bytes, a 2-byte
 // norm and one row of V, nothing else of size.  The context is cut into
-// chunks (one workgroup each); every wave keeps a running (max, sum, o[d])
-// and the partial results are merged wave -> workgroup -> (a small second
-// kernel) across chunks with the usual max/sum-of-exponentials rescaling.
+// chunks (one workgroup each).  A workgroup first computes S q for its query
+// heads itself (S is small and stays in L2; a kernel of its own for this would
+// cost more than the work), turns it into lookup tables, and then streams its
+// keys; every wave keeps a running (max, sum, o[d]) and the partial results
+// are merged wave -> workgroup -> (a small second kernel) across chunks with
+// the usual max/sum-of-exponentials rescaling.
 #include "qjl_common.hpp"
 #include "qjl_lut.hpp"
 
@@ -32,14 +35,16 @@ constexpr int decode_waves(int gt, int m, int elem_bytes) {
 }
 
 struct decode_args {
-  const float* SQ;        // [B,Hq,m]
+  const void* Q;          // [B,Hq,128]
+  const void* S;          // [m,128]
   const uint8_t* bits;    // [B,Hkv,n,m/8]
   const uint16_t* norms;  // [B,Hkv,n]
   const void* V;          // [B,Hkv,n,128]
   float* part;            // [B,Hq,nsplit,132]
   float* out;             // [B,Hq,128]
-  int n, q_heads, kv_heads, groups_per_kv;
+  int n, groups_per_kv;
   int nsplit, chunk;
+  int bk0;                // first (batch, kv head) pair of this launch
   float coef2;            // scale * sqrt(pi/2) / m * log2(e)
 };
 
@@ -67,6 +72,59 @@ template <> struct vtile<f32_t> {
   }
 };
 
+// The query side of Eq. (4), S q, for the GT heads of a workgroup, computed by
+// the workgroup itself: sixteen lanes share a row of S (16 bytes each for the
+// 16-bit types, so one load instruction covers four rows), multiply it with
+// their slice of q and add up inside the 16-lane DPP row.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <typename T> struct slice8 {   // eight consecutive elements, as stored
+  u32x4_t r;
+  __device__ __forceinline__ void load(const void* base, size_t elem) {
+    r = *reinterpret_cast<const u32x4_t*>(static_cast<const uint16_t*>(base) + elem);
+  }
+};
+template <> struct slice8<f32_t> {
+  f32x4_t a, b;
+  __device__ __forceinline__ void load(const void* base, size_t elem) {
+    const f32x4_t* p = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(base) + elem);
+    a = p[0]; b = p[1];
+  }
+};
+__device__ __forceinline__ float dot8(const slice8<bf16_t>& s, const slice8<bf16_t>& q) {
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    bf16x2_t x, y;
+    uint32_t sx = s.r[i], qx = q.r[i];
+    __builtin_memcpy(&x, &sx, 4); __builtin_memcpy(&y, &qx, 4);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(x, y, acc, false);
+  }
+  return acc;
+}
+__device__ __forceinline__ float dot8(const slice8<f16_t>& s, const slice8<f16_t>& q) {
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f16x2_t x, y;
+    uint32_t sx = s.r[i], qx = q.r[i];
+    __builtin_memcpy(&x, &sx, 4); __builtin_memcpy(&y, &qx, 4);
+    acc = __builtin_amdgcn_fdot2(x, y, acc, false);
+  }
+  return acc;
+}
+__device__ __forceinline__ float dot8(const slice8<f32_t>& s, const slice8<f32_t>& q) {
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc = fmaf(s.a[i], q.a[i], acc);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) acc = fmaf(s.b[i], q.b[i], acc);
+  return acc;
+}
+
 template <typename T, int GT, int MW>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
                                   T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
@@ -89,31 +147,49 @@ decode_kernel(decode_args a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps block indices in SGPRs
-  const int unit = blockIdx.x / a.nsplit;
-  const int split = blockIdx.x - unit * a.nsplit;
-  const int gg = unit % a.groups_per_kv;
-  const int bk = unit / a.groups_per_kv;              // b * Hkv + kvh
-  const int b = bk / a.kv_heads, kvh = bk - b * a.kv_heads;
-  const int G = a.groups_per_kv * GT;
-  const size_t hq0 = (size_t)b * a.q_heads + (size_t)kvh * G + (size_t)gg * GT;
+  // grid: x = chunk of the context, y = group of GT query heads, z = (batch, kv head).
+  // Query heads of one kv head are consecutive, so the first head of this
+  // workgroup is ((b * Hkv + kvh) * groups + group) * GT: no division needed.
+  const int split = blockIdx.x;
+  const int bk = a.bk0 + blockIdx.z;                  // b * Hkv + kvh
+  const size_t hq0 = ((size_t)bk * a.groups_per_kv + blockIdx.y) * GT;
 
   const int k_begin = split * a.chunk;
   const int k_end = min(a.n, k_begin + a.chunk);
   const size_t row0 = (size_t)bk * a.n;
   float* pbuf = pbuf_all + wave * 64 * GT;
-  const int r = lane >> 4;                            // row of a 4-row V pass
+  int r = lane >> 4;                                  // row of a 4-row V pass
   const int c = lane & 15;                            // 8-channel slice
 
-  // ---- first block of this wave: start its HBM reads before anything else, so
-  // that they are in flight while the tables are built.  Rows past the chunk
-  // end are clamped (never out of bounds); their weight is 0.
+  // ---- the rows of S and the queries first: loads come back in issue order, and
+  // S q (then the tables) is the first thing that has to be ready
+  constexpr int kRowsPerPass = kNW * 4;                // 16 lanes per row
+  constexpr int kPasses = M / kRowsPerPass;
+  static_assert(M % kRowsPerPass == 0, "whole passes over S");
+  slice8<T> qs[GT], srow[kPasses];
+  {
+    const int c16 = tid & 15, r16 = tid >> 4;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) qs[g].load(a.Q, (hq0 + g) * kD + c16 * 8);
+#pragma unroll
+    for (int u = 0; u < kPasses; ++u) srow[u].load(a.S, (size_t)(u * kRowsPerPass + r16) * kD + c16 * 8);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- then the first block of this wave: its HBM reads are in flight while
+  // the tables are built.  Rows past the chunk end are clamped (never out of
+  // bounds); their weight is 0.
   int k0 = k_begin + wave * 64;
   uint32_t wcur[MW];
-  float ncur = 0.f;
+  uint16_t ncur = 0;   // norm of this lane's key, still as binary16: converting it where it is
+                       // loaded would make the wave wait for the load (and every older one) there
   // V rows in flight per lane: 16 (a whole 64-key block ahead), or 8 where the
   // four-head group needs the registers for its accumulators and tables
   constexpr int VD = GT == 4 ? 8 : 16;
   vtile<T> v[VD];
+  // V loads requested before the tables are built: enough to keep HBM busy
+  // meanwhile, few enough that the rows of S (requested just before them, and
+  // on the critical path) are not held up behind them
+  constexpr int VP = 4;
   // row (4i + r) of the block starting at key kb: uniform base pointer + a
   // 32-bit lane offset, the row clamped to the last key of the chunk
   auto issue_v = [&](int slot, int i, int kb, int last_row) {   // row pass i of block kb -> v[slot]
@@ -121,18 +197,45 @@ decode_kernel(decode_args a) {
     const int rr = min(4 * i + r, last_row);
     v[slot].load(base, (uint32_t)(rr * kD + c * 8));
   };
-  if (k0 < k_end) {
-    const int j = min(k0 + lane, k_end - 1);
+  // No branch around these loads (a wave whose first block lies past the chunk
+  // end reads the chunk's last key instead and never uses it): with straight-line
+  // code the wait for S q below does not have to wait for them as well.
+  const int kf = min(k0, k_end - 1);
+  {
+    const int j = min(kf + lane, k_end - 1);
     load_code<MW>(a.bits, row0 + j, wcur);
-    ncur = f16_bits_to_float(a.norms[row0 + j]);
+    ncur = a.norms[row0 + j];
 #pragma unroll
-    for (int i = 0; i < VD; ++i) issue_v(i, i, k0, k_end - 1 - k0);
+    for (int i = 0; i < VP; ++i) {
+      issue_v(i, i, kf, k_end - 1 - kf);
+      __builtin_amdgcn_sched_barrier(0);   // issue order = use order (see the second half below)
+    }
   }
 
-  for (int e = tid; e < GT * M; e += kNW * 64) sq[e] = a.SQ[hq0 * M + e];
+  __builtin_amdgcn_sched_barrier(0);
+  {
+    const int c16 = tid & 15, r16 = tid >> 4;
+#pragma unroll
+    for (int u = 0; u < kPasses; ++u) {
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        const float t = row16_sum(dot8(srow[u], qs[g]));
+        if (c16 == 0) sq[g * M + u * kRowsPerPass + r16] = t;
+      }
+    }
+  }
   __syncthreads();
   build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
-  // build_lut ends with a barrier: nobody reads `nib` any more.
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = VP; i < VD; ++i) {
+    issue_v(i, i, kf, k_end - 1 - kf);
+    // Loads return in issue order and the loop below consumes the rows in index
+    // order; left alone the scheduler may issue these in any order, and the wait
+    // for row VP inside the loop then has to cover the whole queue, every block.
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // lut_build ends with a barrier: nobody reads `nib` any more.
 
   using PV = typename vecf<GT>::type;
   float m_run[GT], l_lane[GT];
@@ -148,13 +251,13 @@ decode_kernel(decode_args a) {
     // ---- scores of this block: lane <-> key
     const PV s = key_inner<GT, MW>(wcur, lut);
     const bool valid = (k0 + lane) < k_end;
-    const float nu = ncur;
+    const float nu = f16_bits_to_float(ncur);
     // the code registers are free again: fetch the next block's codes and norm
     // into them now, the value pass below hides the latency
     if (have_next) {
       const int j = min(kn + lane, k_end - 1);
       load_code<MW>(a.bits, row0 + j, wcur);
-      ncur = f16_bits_to_float(a.norms[row0 + j]);
+      ncur = a.norms[row0 + j];
     }
     PV alpha, p;
 #pragma unroll
@@ -192,6 +295,12 @@ decode_kernel(decode_args a) {
       v[i % VD].get(x);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += pv * x[e];
+      // The refill overwrites the registers just read.  Tie its address (through r)
+      // to the accumulators: otherwise the compiler may move the load above the last
+      // read, give it fresh registers and copy them back at the loop end -- a copy
+      // that has to wait for the whole queue of loads, every block.
+#pragma unroll
+      for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(r), "+v"(acc[e]));
       if (i + VD < 16) issue_v(i % VD, i + VD, k0, k_end - 1 - k0);   // later row of this block
       else issue_v(i % VD, i + VD - 16, kb_next, lim_next);          // first rows of the next block
       // keep each refill right behind the last use of its registers: hoisting
@@ -310,14 +419,20 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
   }
-  const long units = (long)sh.batch * sh.kv_heads * a.groups_per_kv;
-  const long total = units * plan.nsplit;
-  if (total > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
-  if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
-    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64),
-                          (uint32_t)lds, st, ev0, ev1, 0u, a);
-  else
-    hipLaunchKernelGGL((decode_kernel<T, GT, MW>), dim3((unsigned)total), dim3(kNW * 64), lds, st, a);
+  if (a.groups_per_kv > 65535) return QJL_ERR_UNSUPPORTED;
+  // grid z holds at most 65535 (batch, kv head) pairs: larger caches take several launches
+  const long pairs = (long)sh.batch * sh.kv_heads;
+  for (long bk0 = 0; bk0 < pairs; bk0 += 65535) {
+    const long nz = pairs - bk0 < 65535 ? pairs - bk0 : 65535;
+    const dim3 grid((unsigned)plan.nsplit, (unsigned)a.groups_per_kv, (unsigned)nz);
+    a.bk0 = (int)bk0;
+    const bool first = bk0 == 0, last = bk0 + nz == pairs;
+    if ((ev0 && first) || (ev1 && last))   // the events take the kernels' own start and stop timestamps
+      hipExtLaunchKernelGGL((decode_kernel<T, GT, MW>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+                            first ? ev0 : nullptr, last ? ev1 : nullptr, 0u, a);
+    else
+      hipLaunchKernelGGL((decode_kernel<T, GT, MW>), grid, dim3(kNW * 64), lds, st, a);
+  }
   return launch_status();
 }
 
@@ -391,8 +506,6 @@ bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
   plan->nsplit = (int)nsplit;
   plan->chunk = (int)chunk;
   size_t off = 0;
-  plan->off_sq = off;
-  off = align_up(off + (size_t)sh.batch * sh.q_heads * sh.m * sizeof(float), 256);
   plan->off_part = off;
   off = align_up(off + (size_t)sh.batch * sh.q_heads * nsplit * kPartStride * sizeof(float), 256);
   plan->total = off;
@@ -403,15 +516,12 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
                   const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
                   void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
-  float* SQ = reinterpret_cast<float*>(ws + plan.off_sq);
-  // kernel 1: S q for every query head
-  int rc = launch_project(sh.batch * sh.q_heads, sh.d, sh.m, sh.dtype, Q, S, SQ, st);
-  if (rc != QJL_OK) return rc;
+  int rc = QJL_OK;
   decode_args a;
-  a.SQ = SQ; a.bits = bits; a.norms = norms; a.V = V;
+  a.Q = Q; a.S = S; a.bits = bits; a.norms = norms; a.V = V;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);
   a.out = out;
-  a.n = sh.n; a.q_heads = sh.q_heads; a.kv_heads = sh.kv_heads;
+  a.n = sh.n; a.bk0 = 0;
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
