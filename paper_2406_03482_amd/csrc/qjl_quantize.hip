@@ -109,12 +109,15 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   // ---- loader: thread -> (row lrow + 16u, 16-byte column lcol) of a tile, u = 0..3
   const int lrow = tid >> 4, lcol = tid & 15;
   uint4 pre[4];
+  // addresses are a uniform 64-bit tile base (scalar ALU) plus a 32-bit lane
+  // offset fixed for the whole kernel: no vector ALU work per tile
+  const uint32_t koff = (uint32_t)(lrow * 128 + lcol * 8);
   auto load_tile = [&](int tile) {
     const long row0 = (long)tile * kTok;
     if (row0 + kTok <= rows) {            // uniform: whole tile inside K
-      const uint16_t* kp = K + ((size_t)row0 + lrow) * 128 + lcol * 8;
+      const uint16_t* kp = K + (size_t)row0 * 128;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) pre[u] = *reinterpret_cast<const uint4*>(kp + u * 16 * 128);
+      for (int u = 0; u < 4; ++u) pre[u] = *reinterpret_cast<const uint4*>(kp + (koff + (uint32_t)(u * 16 * 128)));
     } else {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -234,29 +237,19 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
 
     // whole code rows and the tile's norms go to HBM, 16 contiguous bytes per lane
     constexpr int kChunksPerRow = WPT / 4;
+    const long trow0 = (long)tile * kTok;
+    const bool full = trow0 + kTok <= rows;           // uniform
     if (tid < kTok * kChunksPerRow) {
       const int tok = tid / kChunksPerRow, part = tid % kChunksPerRow;
-      const long row = (long)tile * kTok + tok;
-      if (row < rows)
-        *reinterpret_cast<uint4*>(bits + (size_t)row * words_per_row + blockIdx.y * WPT + part * 4) =
-            obuf[buf][tid];
+      if (full || trow0 + tok < rows) {
+        uint32_t* tb0 = bits + (size_t)trow0 * words_per_row;            // uniform
+        const uint32_t off = (uint32_t)(tok * words_per_row + blockIdx.y * WPT + part * 4);
+        *reinterpret_cast<uint4*>(tb0 + off) = obuf[buf][tid];
+      }
     }
-    if (blockIdx.y == 0 && tid >= 248) {              // 8 lanes x 8 norms
-      const int q = tid - 248;
-      const long row = (long)tile * kTok + q * 8;
-      uint32_t pk[4];
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const uint32_t lo = float_to_f16_bits(sqrtf(nsq[buf][q * 8 + 2 * t]));
-        const uint32_t hi = float_to_f16_bits(sqrtf(nsq[buf][q * 8 + 2 * t + 1]));
-        pk[t] = lo | (hi << 16);
-      }
-      if (row + 8 <= rows) {
-        *reinterpret_cast<uint4*>(norms + row) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-      } else {
-        for (int t = 0; t < 8; ++t)
-          if (row + t < rows) norms[row + t] = (uint16_t)(pk[t >> 1] >> (16 * (t & 1)));
-      }
+    if (blockIdx.y == 0 && wave == 3) {               // one wave, one key per lane: a single square root
+      const uint16_t nu = float_to_f16_bits(sqrtf(nsq[buf][lane]));
+      if (full || trow0 + lane < rows) (norms + trow0)[lane] = nu;
     }
   }
 }
