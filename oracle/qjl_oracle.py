@@ -36,6 +36,19 @@ Readings of points the paper leaves open (all restated where they are used):
     vector, by determinism and by distribution tests only: beyond that the
     *values* of S are "parity unpinned" (any i.i.d. N(0,1) matrix is a valid
     S).  Every other function here is pinned by tests/test_oracle_pins.py.
+  * Outlier channels (Section 4.1, "Outliers"; end of Section 1): the paper
+    says that the channels are identified in the prompt phase and that two
+    independent copies of the quantizer are applied to outliers and inliers,
+    the outlier copy with more bits per coordinate; it gives no selection
+    rule, no sizes and no layout.  Read here as: per (batch, kv head) the
+    `count` channels with the largest mean |k| over the prompt's tokens
+    (Figure 2 ranks channels by exactly that), ties to the lower index; the
+    inlier copy sees the key with those coordinates set to zero, the outlier
+    copy sees only those coordinates (left in place), each with its own
+    i.i.d. sketch ([m_in,d] and [m_out,d]) and its own binary16 norm; the
+    query is split the same way and the two Eq. (4) estimates are added; a
+    cache row is the inlier code followed by the outlier code.  These
+    functions are pinned by tests/test_oracle_dual_pins.py.
 
 Array conventions (all dense, C order):
     K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
@@ -239,3 +252,82 @@ def prod_qjl(q: np.ndarray, k: np.ndarray, S: np.ndarray) -> float:
     m = S.shape[0]
     h = np.where(S @ k >= 0.0, 1.0, -1.0)
     return SQRT_HALF_PI / m * math.sqrt(float(k @ k)) * float((S @ q) @ h)
+
+
+# --------------------------------------------------------------------------
+# Section 4.1 "Outliers": two independent quantizers for outlier and inlier
+# channels.  Everything below is the single-sketch definitions above applied
+# to two sub-vectors; only the channel choice and the split are new.
+# --------------------------------------------------------------------------
+def select_outlier_channels(K: np.ndarray, count: int) -> np.ndarray:
+    """For every (batch, kv head): the `count` channels whose mean |k| over the
+    n tokens of K [B,Hkv,n,d] is largest, in decreasing order of that mean,
+    ties to the lower channel index.  Returns int64 [B,Hkv,count]."""
+    K = np.asarray(K, dtype=np.float64)
+    B, H, n, d = K.shape
+    if not 0 <= count <= d:
+        raise ValueError("count must be in [0, d]")
+    mean_abs = np.mean(np.abs(K), axis=2)                  # [B,H,d]
+    out = np.empty((B, H, count), dtype=np.int64)
+    for b in range(B):
+        for h in range(H):
+            order = sorted(range(d), key=lambda t: (-mean_abs[b, h, t], t))
+            out[b, h] = order[:count]
+    return out
+
+
+def split_channels(X: np.ndarray, channels: np.ndarray):
+    """X [B,H,...,d] -> (X_in, X_out) with X_in + X_out = X: X_out keeps only the
+    coordinates listed in channels[b, h // (H // Hkv)], X_in has them zeroed.
+    (H may be the number of query heads: a query head uses the channels of its
+    kv head.)"""
+    X = np.asarray(X, dtype=np.float64)
+    channels = np.asarray(channels, dtype=np.int64)
+    B, H = X.shape[:2]
+    Hkv = channels.shape[1]
+    if H % Hkv:
+        raise ValueError("head count must be a multiple of the kv head count")
+    G = H // Hkv
+    X_out = np.zeros_like(X)
+    for b in range(B):
+        for h in range(H):
+            idx = channels[b, h // G]
+            if len(set(idx.tolist())) != len(idx):
+                raise ValueError("outlier channels must be distinct")
+            X_out[b, h][..., idx] = X[b, h][..., idx]
+    return X - X_out, X_out
+
+
+def quantize_keys_dual(K: np.ndarray, S_in: np.ndarray, S_out: np.ndarray,
+                       channels: np.ndarray):
+    """Two independent copies of Algorithm 1 steps 3-4, one on the inlier part
+    of every key and one on its outlier part.  Returns
+
+        bits    uint8  [B,Hkv,n,(m_in+m_out)/8]   inlier code, then outlier code
+        nu_in   float16[B,Hkv,n]   ||k_in||_2     nu_out float16 ||k_out||_2
+        P_in, P_out                               the projections (float64)
+    """
+    K_in, K_out = split_channels(K, channels)
+    b_in, nu_in, P_in = quantize_keys(K_in, S_in)
+    b_out, nu_out, P_out = quantize_keys(K_out, S_out)
+    return np.concatenate([b_in, b_out], axis=-1), nu_in, nu_out, P_in, P_out
+
+
+def estimate_scores_dual(Q: np.ndarray, S_in: np.ndarray, S_out: np.ndarray,
+                         channels: np.ndarray, bits: np.ndarray, nu_in16: np.ndarray,
+                         nu_out16: np.ndarray, scale: float = 1.0) -> np.ndarray:
+    """scale * (Prod_QJL on the inlier parts + Prod_QJL on the outlier parts)
+    for every query head and cached key: Q [B,Hq,d] -> [B,Hq,n]."""
+    m_in = np.asarray(S_in).shape[0]
+    Q_in, Q_out = split_channels(Q, channels)
+    bits = np.asarray(bits, dtype=np.uint8)
+    s_in = estimate_scores(project_query(Q_in, S_in), bits[..., : m_in // 8], nu_in16, scale)
+    s_out = estimate_scores(project_query(Q_out, S_out), bits[..., m_in // 8:], nu_out16, scale)
+    return s_in + s_out
+
+
+def decode_attention_dual(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, V,
+                          scale: float = 1.0) -> np.ndarray:
+    """One decode step on a cache quantized by `quantize_keys_dual`."""
+    return attention_from_scores(
+        estimate_scores_dual(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, scale), V)
