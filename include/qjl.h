@@ -106,8 +106,8 @@ int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits,
                const uint16_t* norms, float* out, void* stream);
 
 /*
- * Bytes of device scratch qjl_decode_attention needs for this shape (query
- * projections and per-chunk softmax partials).  Returns 0
+ * Bytes of device scratch qjl_decode_attention needs for this shape
+ * (per-chunk softmax partials).  Returns 0
  * for an invalid or unsupported shape.  Host only.
  */
 size_t qjl_decode_workspace_bytes(const qjl_shape* shape);
@@ -133,9 +133,9 @@ int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S,
  * qjl_decode_attention, plus kernel timing without a profiler: the two
  * caller-owned events (hipEvent_t passed as void*, created with timing
  * enabled; either may be NULL) receive the start and the stop timestamp of
- * the attention kernel itself (Algorithm 1 EstimateScores + Eq. (1)), the
- * way a profiler sees that dispatch; the small query-projection kernel
- * before it and the chunk-merge kernel after it are outside the interval.
+ * the attention kernel itself (S q, Algorithm 1 EstimateScores, Eq. (1)), the
+ * way a profiler sees that dispatch; the chunk-merge kernel after it is
+ * outside the interval.
  * hipEventElapsedTime(before, after) is valid once `after` has completed.
  * Everything else is exactly qjl_decode_attention.
  */
@@ -143,6 +143,76 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
                                const uint8_t* bits, const uint16_t* norms, const void* V,
                                float* out, void* workspace, size_t workspace_bytes,
                                void* stream, void* event_before, void* event_after);
+
+/* ------------------------------------------------------------------------
+ * Outlier channels (Section 4.1, "Outliers"; end of Section 1): certain fixed
+ * channels of the keys of a head are much larger than the rest; they are
+ * identified in the prompt phase and two independent copies of the quantizer
+ * are applied to the outlier and to the inlier coordinates, the outlier copy
+ * with more bits per coordinate.  The paper fixes no selection rule, sizes or
+ * layout; the calls below use:
+ *   - per (batch, kv head) the `count` channels with the largest mean |k| over
+ *     the n tokens, in decreasing order, ties to the lower channel index;
+ *   - inlier copy: the key with those coordinates set to zero, sketch
+ *     S_in[m,d]; outlier copy: only those coordinates (in place), sketch
+ *     S_out[m_out,d]; a binary16 norm of each part; the query is split the
+ *     same way and the two Eq. (4) estimates are added;
+ *   - a cache row is the m/8 bytes of the inlier code followed by the
+ *     m_out/8 bytes of the outlier code.
+ * In these calls shape->m is the inlier sketch size.
+ * ---------------------------------------------------------------------- */
+
+/* Bytes of device scratch qjl_select_outliers needs (partial sums).  Host only. */
+size_t qjl_outlier_workspace_bytes(const qjl_shape* shape);
+
+/*
+ * channels[B,Hkv,count] (int32, device) <- for every (batch, kv head) the
+ * `count` channels of K[B,Hkv,n,d] with the largest sum_j |K[j,t]| (fp32
+ * accumulation in a fixed order), largest first, ties to the lower index.
+ * 1 <= count <= min(d, 16).  workspace: caller-owned device memory of at least
+ * qjl_outlier_workspace_bytes(shape) bytes; asynchronous on `stream`.
+ */
+int qjl_select_outliers(const qjl_shape* shape, const void* K, int count, int32_t* channels,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * S_dual[B,Hkv,m+m_out,d] (device, shape->dtype) <- per (batch, kv head) the
+ * stacked sketch: rows [0,m) are S_in[m,d] with that head's outlier columns
+ * set to zero, rows [m,m+m_out) are S_out[m_out,d] with every other column set
+ * to zero.  sign(S_dual k) is then the inlier code followed by the outlier
+ * code, and S_dual q the two query projections.  Channel entries outside
+ * [0,d) are ignored; count == 0 (channels may then be NULL) leaves S_in whole
+ * and the outlier rows zero.
+ */
+int qjl_make_dual_sketch(const qjl_shape* shape, int m_out, const void* S_in, const void* S_out,
+                         const int32_t* channels, int count, void* S_dual, void* stream);
+
+/*
+ * Algorithm 1 steps 3-4, twice per key: bits[B,Hkv,n,(m+m_out)/8] <- packed
+ * sign(S_dual k) (same bit order as qjl_quantize_keys), norms_in[B,Hkv,n] <-
+ * ||k without its head's outlier channels||, norms_out[B,Hkv,n] <- ||those
+ * channels of k||, both binary16.  (m+m_out) % 32 == 0.  Channel entries
+ * outside [0,d) are clamped into range.
+ */
+int qjl_quantize_keys_dual(const qjl_shape* shape, int m_out, const void* K, const void* S_dual,
+                           const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                           uint16_t* norms_out, void* stream);
+
+/* Workspace of qjl_decode_attention_dual; 0 for unsupported shapes.  Host only. */
+size_t qjl_decode_dual_workspace_bytes(const qjl_shape* shape, int m_out);
+
+/*
+ * qjl_decode_attention on a cache written by qjl_quantize_keys_dual:
+ *   score_j = scale * sqrt(pi/2) * ( norms_in[j]/m * <S_in q_in, inlier bits_j>
+ *                                  + norms_out[j]/m_out * <S_out q_out, outlier bits_j> )
+ * then softmax and Eq. (1).  S_dual as written by qjl_make_dual_sketch.
+ * Supported: d == 128, m in {128, 256}, m_out == 128.  Workspace rules as for
+ * qjl_decode_attention.
+ */
+int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, const void* S_dual,
+                              const uint8_t* bits, const uint16_t* norms_in,
+                              const uint16_t* norms_out, const void* V, float* out, void* workspace,
+                              size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -63,6 +63,19 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.qjl_decode_attention_timed.restype = ctypes.c_int
     L.qjl_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    ip = ctypes.c_int
+    L.qjl_outlier_workspace_bytes.restype = ctypes.c_size_t
+    L.qjl_outlier_workspace_bytes.argtypes = [sp]
+    L.qjl_select_outliers.restype = ctypes.c_int
+    L.qjl_select_outliers.argtypes = [sp, vp, ip, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_make_dual_sketch.restype = ctypes.c_int
+    L.qjl_make_dual_sketch.argtypes = [sp, ip, vp, vp, vp, ip, vp, vp]
+    L.qjl_quantize_keys_dual.restype = ctypes.c_int
+    L.qjl_quantize_keys_dual.argtypes = [sp, ip, vp, vp, vp, ip, vp, vp, vp, vp]
+    L.qjl_decode_dual_workspace_bytes.restype = ctypes.c_size_t
+    L.qjl_decode_dual_workspace_bytes.argtypes = [sp, ip]
+    L.qjl_decode_attention_dual.restype = ctypes.c_int
+    L.qjl_decode_attention_dual.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -190,4 +203,104 @@ def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, n
         _check("qjl_decode_attention", lib().qjl_decode_attention(*args))
     else:
         _check("qjl_decode_attention_timed", lib().qjl_decode_attention_timed(*args, events[0], events[1]))
+    return out
+
+
+# ---- outlier channels (Section 4.1): two quantizers per key
+def qjl_select_outliers(K: torch.Tensor, count: int, channels: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """K[B,Hkv,n,d] -> int32 [B,Hkv,count]: channels with the largest mean |k|, largest first."""
+    B, Hkv, n, d = K.shape
+    sh = _shape(B, Hkv, Hkv, n, d, 32, _tag(K))
+    need = int(lib().qjl_outlier_workspace_bytes(ctypes.byref(sh)))
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=K.device)
+    if channels is None:
+        channels = torch.empty((B, Hkv, count), dtype=torch.int32, device=K.device)
+    if tuple(channels.shape) != (B, Hkv, count) or channels.dtype != torch.int32:
+        raise ValueError("channels must be int32 [B,Hkv,count]")
+    _check("qjl_select_outliers",
+           lib().qjl_select_outliers(ctypes.byref(sh), _dev(K, "K"), count, _dev(channels, "channels"),
+                                     _dev(workspace, "workspace"),
+                                     workspace.numel() * workspace.element_size(), _stream(K)))
+    return channels
+
+
+def qjl_make_dual_sketch(S_in: torch.Tensor, S_out: torch.Tensor, channels: torch.Tensor,
+                         S_dual: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """S_in[m,d], S_out[m_out,d], channels int32 [B,Hkv,count] -> S_dual[B,Hkv,m+m_out,d]."""
+    m, d = S_in.shape
+    m_out = S_out.shape[0]
+    B, Hkv, count = channels.shape
+    if S_out.shape[1] != d or S_out.dtype != S_in.dtype or channels.dtype != torch.int32:
+        raise ValueError("S_out must be [m_out,d] with the dtype of S_in; channels int32")
+    if S_dual is None:
+        S_dual = torch.empty((B, Hkv, m + m_out, d), dtype=S_in.dtype, device=S_in.device)
+    sh = _shape(B, Hkv, Hkv, 1, d, m, _tag(S_in))
+    _check("qjl_make_dual_sketch",
+           lib().qjl_make_dual_sketch(ctypes.byref(sh), m_out, _dev(S_in, "S_in"), _dev(S_out, "S_out"),
+                                      _dev(channels, "channels"), count, _dev(S_dual, "S_dual"),
+                                      _stream(S_in)))
+    return S_dual
+
+
+def qjl_quantize_keys_dual(K: torch.Tensor, S_dual: torch.Tensor, channels: torch.Tensor, m_out: int,
+                           bits: Optional[torch.Tensor] = None, norms_in: Optional[torch.Tensor] = None,
+                           norms_out: Optional[torch.Tensor] = None):
+    """K[B,Hkv,n,d], S_dual[B,Hkv,m+m_out,d] -> (bits uint8 [B,Hkv,n,(m+m_out)/8], norms_in, norms_out)."""
+    B, Hkv, n, d = K.shape
+    mt = S_dual.shape[2]
+    count = channels.shape[2]
+    if tuple(S_dual.shape) != (B, Hkv, mt, d) or S_dual.dtype != K.dtype or not 0 < m_out < mt:
+        raise ValueError("S_dual must be [B,Hkv,m+m_out,d] with the dtype of K")
+    if tuple(channels.shape) != (B, Hkv, count) or channels.dtype != torch.int32:
+        raise ValueError("channels must be int32 [B,Hkv,count]")
+    if bits is None:
+        bits = torch.empty((B, Hkv, n, mt // 8), dtype=torch.uint8, device=K.device)
+    if norms_in is None:
+        norms_in = torch.empty((B, Hkv, n), dtype=torch.float16, device=K.device)
+    if norms_out is None:
+        norms_out = torch.empty((B, Hkv, n), dtype=torch.float16, device=K.device)
+    sh = _shape(B, Hkv, Hkv, n, d, mt - m_out, _tag(K))
+    _check("qjl_quantize_keys_dual",
+           lib().qjl_quantize_keys_dual(ctypes.byref(sh), m_out, _dev(K, "K"), _dev(S_dual, "S_dual"),
+                                        _dev(channels, "channels"), count, _dev(bits, "bits"),
+                                        _dev(norms_in, "norms_in"), _dev(norms_out, "norms_out"),
+                                        _stream(K)))
+    return bits, norms_in, norms_out
+
+
+def qjl_decode_dual_workspace_bytes(batch: int, q_heads: int, kv_heads: int, n: int, d: int, m: int,
+                                    m_out: int, dtype: torch.dtype = torch.bfloat16) -> int:
+    sh = _shape(batch, q_heads, kv_heads, n, d, m, _DTYPE_TAG[dtype])
+    return int(lib().qjl_decode_dual_workspace_bytes(ctypes.byref(sh), m_out))
+
+
+def qjl_decode_attention_dual(Q: torch.Tensor, S_dual: torch.Tensor, bits: torch.Tensor,
+                              norms_in: torch.Tensor, norms_out: torch.Tensor, V: torch.Tensor,
+                              m_out: int, scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decode step on a two-part cache: -> float32 [B,Hq,d]."""
+    B, Hq, d = Q.shape
+    _, Hkv, n, _ = V.shape
+    mt = S_dual.shape[2]
+    m = mt - m_out
+    if V.dtype != Q.dtype or S_dual.dtype != Q.dtype:
+        raise ValueError("Q, S_dual and V must share one dtype")
+    if tuple(S_dual.shape) != (B, Hkv, mt, d) or tuple(bits.shape) != (B, Hkv, n, mt // 8):
+        raise ValueError("S_dual/bits do not match V")
+    if tuple(norms_in.shape) != (B, Hkv, n) or tuple(norms_out.shape) != (B, Hkv, n):
+        raise ValueError("norms do not match V")
+    need = qjl_decode_dual_workspace_bytes(B, Hq, Hkv, n, d, m, m_out, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, n, d, m, _tag(Q), scale)
+    _check("qjl_decode_attention_dual",
+           lib().qjl_decode_attention_dual(ctypes.byref(sh), m_out, _dev(Q, "Q"), _dev(S_dual, "S_dual"),
+                                           _dev(bits, "bits"), _dev(norms_in, "norms_in"),
+                                           _dev(norms_out, "norms_out"), _dev(V, "V"), _dev(out, "out"),
+                                           _dev(workspace, "workspace"),
+                                           workspace.numel() * workspace.element_size(), _stream(Q)))
     return out

@@ -77,7 +77,7 @@ int qjl_scores(const qjl_shape* shape, const float* SQ, const uint8_t* bits, con
 size_t qjl_decode_workspace_bytes(const qjl_shape* shape) {
   if (check_shape(shape) != QJL_OK) return 0;
   decode_plan plan;
-  if (!plan_decode(*shape, &plan)) return 0;
+  if (!plan_decode(*shape, 0, &plan)) return 0;
   return plan.total;
 }
 
@@ -97,12 +97,80 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
   if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(V) || !ptr_ok(out))
     return QJL_ERR_INVALID_ARG;
   decode_plan plan;
-  if (!plan_decode(*shape, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, plan, Q, S, bits, norms, V, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
+}
+
+size_t qjl_outlier_workspace_bytes(const qjl_shape* shape) {
+  if (check_shape(shape) != QJL_OK) return 0;
+  return outlier_workspace_bytes(*shape);
+}
+
+int qjl_select_outliers(const qjl_shape* shape, const void* K, int count, int32_t* channels,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(K) || channels == nullptr) return QJL_ERR_INVALID_ARG;
+  if (count < 1 || count > 16 || count > shape->d) return QJL_ERR_INVALID_ARG;
+  if (shape->d > 8192) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < outlier_workspace_bytes(*shape)) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return QJL_ERR_INVALID_ARG;
+  return launch_select_outliers(*shape, K, count, channels, workspace, static_cast<hipStream_t>(stream));
+}
+
+int qjl_make_dual_sketch(const qjl_shape* shape, int m_out, const void* S_in, const void* S_out,
+                         const int32_t* channels, int count, void* S_dual, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(S_in) || !ptr_ok(S_out) || !ptr_ok(S_dual) || (channels == nullptr && count > 0))
+    return QJL_ERR_INVALID_ARG;
+  if (m_out < 1 || count < 0 || count > 16 || count > shape->d) return QJL_ERR_INVALID_ARG;
+  if ((long)(shape->m + m_out) * shape->d > (1L << 30) || shape->d > 8192) return QJL_ERR_UNSUPPORTED;
+  return launch_make_dual_sketch(*shape, m_out, S_in, S_out, channels, count, S_dual,
+                                 static_cast<hipStream_t>(stream));
+}
+
+int qjl_quantize_keys_dual(const qjl_shape* shape, int m_out, const void* K, const void* S_dual,
+                           const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                           uint16_t* norms_out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(K) || !ptr_ok(S_dual) || !ptr_ok(bits) || !ptr_ok(norms_in) || !ptr_ok(norms_out) ||
+      (channels == nullptr && count > 0))
+    return QJL_ERR_INVALID_ARG;
+  if (m_out < 1 || count < 0 || count > 16 || count > shape->d) return QJL_ERR_INVALID_ARG;
+  if ((shape->m + m_out) % 32 != 0 || shape->d > 1024) return QJL_ERR_UNSUPPORTED;
+  return launch_quantize_dual(*shape, m_out, K, S_dual, channels, count, bits, norms_in, norms_out,
+                              static_cast<hipStream_t>(stream));
+}
+
+size_t qjl_decode_dual_workspace_bytes(const qjl_shape* shape, int m_out) {
+  if (check_shape(shape) != QJL_OK || m_out < 1) return 0;
+  decode_plan plan;
+  if (!plan_decode(*shape, m_out, &plan)) return 0;
+  return plan.total;
+}
+
+int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, const void* S_dual,
+                              const uint8_t* bits, const uint16_t* norms_in,
+                              const uint16_t* norms_out, const void* V, float* out, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S_dual) || !ptr_ok(bits) || !ptr_ok(norms_in) || !ptr_ok(norms_out) ||
+      !ptr_ok(V) || !ptr_ok(out))
+    return QJL_ERR_INVALID_ARG;
+  if (m_out < 1) return QJL_ERR_INVALID_ARG;
+  decode_plan plan;
+  if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, out, workspace,
+                       static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 }  // extern "C"

@@ -128,6 +128,14 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 int launch_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, hipStream_t st);
 int launch_quantize(const qjl_shape& sh, const void* K, const void* S, uint8_t* bits,
                     uint16_t* norms, hipStream_t st);
+int launch_quantize_dual(const qjl_shape& sh, int m_out, const void* K, const void* S_dual,
+                         const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                         uint16_t* norms_out, hipStream_t st);
+size_t outlier_workspace_bytes(const qjl_shape& sh);
+int launch_select_outliers(const qjl_shape& sh, const void* K, int count, int32_t* channels,
+                           void* workspace, hipStream_t st);
+int launch_make_dual_sketch(const qjl_shape& sh, int m_out, const void* S_in, const void* S_out,
+                            const int32_t* channels, int count, void* S_dual, hipStream_t st);
 int launch_project(int rows, int d, int m, int dtype, const void* Q, const void* S, float* SQ,
                    hipStream_t st);
 int launch_scores(const qjl_shape& sh, const float* SQ, const uint8_t* bits,
@@ -140,10 +148,13 @@ struct decode_plan {
   size_t off_part;   // byte offset of the per-chunk records inside the workspace
   size_t total;      // bytes
 };
-bool plan_decode(const qjl_shape& sh, decode_plan* plan);
-int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, const void* S,
-                  const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
-                  void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
+// m_out = 0: one code per key (sh.m bits, one shared sketch S[m,d]).  m_out > 0: a key's
+// code is sh.m + m_out bits of two independent instances with a norm each, and S
+// holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).
+bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
+int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
+                  const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
+                  float* out, void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
 int device_cu_count();
 
 }  // namespace qjl

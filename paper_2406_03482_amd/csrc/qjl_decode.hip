@@ -36,16 +36,19 @@ constexpr int decode_waves(int gt, int m, int elem_bytes) {
 
 struct decode_args {
   const void* Q;          // [B,Hq,128]
-  const void* S;          // [m,128]
-  const uint8_t* bits;    // [B,Hkv,n,m/8]
+  const void* S;          // [m,128], or one [m,128] block per (batch, kv head) if s_head_stride != 0
+  const uint8_t* bits;    // [B,Hkv,n,m/8]   (m = all code bits of a key)
   const uint16_t* norms;  // [B,Hkv,n]
+  const uint16_t* norms2; // [B,Hkv,n] norm of the outlier part (two-part codes only)
+  size_t s_head_stride;   // elements between the sketches of consecutive (batch, kv head) pairs
   const void* V;          // [B,Hkv,n,128]
   float* part;            // [B,Hq,nsplit,132]
   float* out;             // [B,Hq,128]
   int n, groups_per_kv;
   int nsplit, chunk;
   int bk0;                // first (batch, kv head) pair of this launch
-  float coef2;            // scale * sqrt(pi/2) / m * log2(e)
+  float coef2;            // scale * sqrt(pi/2) / m * log2(e); m = bits of the (first) code part
+  float coef2b;           // the same for the second part
 };
 
 // 16 bytes of V -> 8 floats (16-bit types) ...
@@ -125,11 +128,17 @@ __device__ __forceinline__ float dot8(const slice8<f32_t>& s, const slice8<f32_t
   return acc;
 }
 
-template <typename T, int GT, int MW>
+// MW = 32-bit words of a key's code.  MWB = 0: one QJL instance.  MWB > 0: the
+// last MWB words belong to a second, independent instance (Section 4.1: outlier
+// channels) with its own norm; a.S then points to per-head sketches whose rows
+// are already restricted to the coordinates of each instance, so S q needs no
+// special case, and the two partial inner products are weighted separately.
+template <typename T, int GT, int MW, int MWB>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
                                   T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
+  constexpr int MWA = MW - MWB;                        // words of the first instance
   extern __shared__ float4 smem4[];
   float* smem = reinterpret_cast<float*>(smem4);
   constexpr int M = MW * 32;
@@ -171,8 +180,9 @@ decode_kernel(decode_args a) {
     const int c16 = tid & 15, r16 = tid >> 4;
 #pragma unroll
     for (int g = 0; g < GT; ++g) qs[g].load(a.Q, (hq0 + g) * kD + c16 * 8);
+    const size_t s0 = (size_t)bk * a.s_head_stride;
 #pragma unroll
-    for (int u = 0; u < kPasses; ++u) srow[u].load(a.S, (size_t)(u * kRowsPerPass + r16) * kD + c16 * 8);
+    for (int u = 0; u < kPasses; ++u) srow[u].load(a.S, s0 + (size_t)(u * kRowsPerPass + r16) * kD + c16 * 8);
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- then the first block of this wave: its HBM reads are in flight while
@@ -182,6 +192,7 @@ decode_kernel(decode_args a) {
   uint32_t wcur[MW];
   uint16_t ncur = 0;   // norm of this lane's key, still as binary16: converting it where it is
                        // loaded would make the wave wait for the load (and every older one) there
+  uint16_t ncur2 = 0;  // norm of the second code part
   // V rows in flight per lane: 16 (a whole 64-key block ahead), or 8 where the
   // four-head group needs the registers for its accumulators and tables
   constexpr int VD = GT == 4 ? 8 : 16;
@@ -205,6 +216,7 @@ decode_kernel(decode_args a) {
     const int j = min(kf + lane, k_end - 1);
     load_code<MW>(a.bits, row0 + j, wcur);
     ncur = a.norms[row0 + j];
+    if constexpr (MWB > 0) ncur2 = a.norms2[row0 + j];
 #pragma unroll
     for (int i = 0; i < VP; ++i) {
       issue_v(i, i, kf, k_end - 1 - kf);
@@ -249,20 +261,26 @@ decode_kernel(decode_args a) {
     const int kn = k0 + kNW * 64;
     const bool have_next = kn < k_end;
     // ---- scores of this block: lane <-> key
-    const PV s = key_inner<GT, MW>(wcur, lut);
+    const PV s = key_inner<GT, MW, 0, MWA>(wcur, lut);
+    PV s2 = 0.f;
+    if constexpr (MWB > 0) s2 = key_inner<GT, MW, MWA, MW>(wcur, lut);
     const bool valid = (k0 + lane) < k_end;
-    const float nu = f16_bits_to_float(ncur);
+    const float nu = f16_bits_to_float(ncur) * a.coef2;
+    const float nu2 = MWB > 0 ? f16_bits_to_float(ncur2) * a.coef2b : 0.f;
     // the code registers are free again: fetch the next block's codes and norm
     // into them now, the value pass below hides the latency
     if (have_next) {
       const int j = min(kn + lane, k_end - 1);
       load_code<MW>(a.bits, row0 + j, wcur);
       ncur = a.norms[row0 + j];
+      if constexpr (MWB > 0) ncur2 = a.norms2[row0 + j];
     }
     PV alpha, p;
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      const float sg = valid ? vget<GT>(s, g) * nu * a.coef2 : -INFINITY;   // log2 domain
+      float sv = vget<GT>(s, g) * nu;                                       // log2 domain
+      if constexpr (MWB > 0) sv = fmaf(vget<GT>(s2, g), nu2, sv);
+      const float sg = valid ? sv : -INFINITY;
       const float m_new = fmaxf(m_run[g], wave_max(sg));
       const float al = __builtin_amdgcn_exp2f(m_run[g] - m_new);
       const float pg = __builtin_amdgcn_exp2f(sg - m_new);
@@ -407,14 +425,14 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
   if (half == 0) out[head * kD + ch] = (O + s_o[ch]) / (L + s_lsum);
 }
 
-template <typename T, int GT, int MW>
+template <typename T, int GT, int MW, int MWB>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   static bool attr_set = false;
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   const size_t lds = decode_lds_bytes(GT, MW * 32);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
@@ -428,33 +446,39 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
     a.bk0 = (int)bk0;
     const bool first = bk0 == 0, last = bk0 + nz == pairs;
     if ((ev0 && first) || (ev1 && last))   // the events take the kernels' own start and stop timestamps
-      hipExtLaunchKernelGGL((decode_kernel<T, GT, MW>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+      hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
                             first ? ev0 : nullptr, last ? ev1 : nullptr, 0u, a);
     else
-      hipLaunchKernelGGL((decode_kernel<T, GT, MW>), grid, dim3(kNW * 64), lds, st, a);
+      hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), lds, st, a);
   }
   return launch_status();
 }
 
-template <typename T, int MW>
+template <typename T, int MW, int MWB>
 int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   switch (plan.gt) {
-    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    default: return launch_t<T, 1, MW>(sh, plan, a, st, ev0, ev1);
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW, MWB>(sh, plan, a, st, ev0, ev1);
   }
 }
 
+// m = bits of the (first) code part, m_out = bits of the second part (0: none)
 template <typename T>
-int launch_m(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
+int launch_m(const qjl_shape& sh, int m_out, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
-  switch (sh.m) {
-    case 128: return launch_g<T, 4>(sh, plan, a, st, ev0, ev1);
-    case 256: return launch_g<T, 8>(sh, plan, a, st, ev0, ev1);
-    case 512: return launch_g<T, 16>(sh, plan, a, st, ev0, ev1);
-    default: return QJL_ERR_UNSUPPORTED;
+  if (m_out == 0) {
+    switch (sh.m) {
+      case 128: return launch_g<T, 4, 0>(sh, plan, a, st, ev0, ev1);
+      case 256: return launch_g<T, 8, 0>(sh, plan, a, st, ev0, ev1);
+      case 512: return launch_g<T, 16, 0>(sh, plan, a, st, ev0, ev1);
+      default: return QJL_ERR_UNSUPPORTED;
+    }
   }
+  if (m_out == 128 && sh.m == 128) return launch_g<T, 8, 4>(sh, plan, a, st, ev0, ev1);
+  if (m_out == 128 && sh.m == 256) return launch_g<T, 12, 4>(sh, plan, a, st, ev0, ev1);
+  return QJL_ERR_UNSUPPORTED;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -476,21 +500,26 @@ int device_cu_count() {
 
 // How the context is cut up.  One "unit" is a (batch, kv head, group of GT
 // query heads); it gets nsplit workgroups of `chunk` keys each.
-bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
+bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
   if (sh.d != kD) return false;
-  if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
+  if (m_out == 0) {
+    if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
+  } else if (m_out != 128 || (sh.m != 128 && sh.m != 256)) {
+    return false;
+  }
+  const int mt = sh.m + m_out;                      // all code bits of a key
   const int G = sh.q_heads / sh.kv_heads;
   int gt = 1;
-  if (G % 4 == 0 && sh.m * 4 <= 1024) gt = 4;
-  else if (G % 2 == 0 && sh.m * 2 <= 1024) gt = 2;
+  if (G % 4 == 0 && mt * 4 <= 1024) gt = 4;
+  else if (G % 2 == 0 && mt * 2 <= 1024) gt = 2;
   const long units = (long)sh.batch * sh.kv_heads * (G / gt);
-  const size_t lds = decode_lds_bytes(gt, sh.m);
+  const size_t lds = decode_lds_bytes(gt, mt);
   long occ = (160 * 1024) / (long)lds;              // workgroups per CU by LDS
   if (occ < 1) occ = 1;
   if (occ > 4) occ = 4;
   const long slots = (long)device_cu_count() * occ;
   long nsplit = (slots + units - 1) / units;
-  const long min_chunk = 64L * decode_waves(gt, sh.m, sh.dtype == QJL_F32 ? 4 : 2);  // one 64-key block per wave
+  const long min_chunk = 64L * decode_waves(gt, mt, sh.dtype == QJL_F32 ? 4 : 2);  // one 64-key block per wave
   long max_split = ((long)sh.n + min_chunk - 1) / min_chunk;
   if (nsplit > max_split) nsplit = max_split;
   if (nsplit > 512) nsplit = 512;
@@ -512,13 +541,16 @@ bool plan_decode(const qjl_shape& sh, decode_plan* plan) {
   return true;
 }
 
-int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, const void* S,
-                  const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
-                  void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
+int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
+                  const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
+                  float* out, void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
   decode_args a;
   a.Q = Q; a.S = S; a.bits = bits; a.norms = norms; a.V = V;
+  a.norms2 = norms_out;
+  a.s_head_stride = m_out > 0 ? (size_t)(sh.m + m_out) * kD : 0;
+  a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);
   a.out = out;
   a.n = sh.n; a.bk0 = 0;
@@ -526,9 +558,9 @@ int launch_decode(const qjl_shape& sh, const decode_plan& plan, const void* Q, c
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
   switch (sh.dtype) {
-    case QJL_F32: rc = launch_m<f32_t>(sh, plan, a, st, ev_before, ev_after); break;
-    case QJL_F16: rc = launch_m<f16_t>(sh, plan, a, st, ev_before, ev_after); break;
-    default: rc = launch_m<bf16_t>(sh, plan, a, st, ev_before, ev_after); break;
+    case QJL_F32: rc = launch_m<f32_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
+    case QJL_F16: rc = launch_m<f16_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
+    default: rc = launch_m<bf16_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
   }
   if (rc != QJL_OK || plan.nsplit == 1) return rc;
   // kernel 3: merge the chunks

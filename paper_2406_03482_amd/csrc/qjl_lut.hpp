@@ -74,13 +74,14 @@ __device__ __forceinline__ void build_lut(const float* sq, float* nib, float* lu
 }
 
 // <S q_g, signs of one key> for g < GT, from the key's MW code words.
-template <int GT, int MW>
+// Words [W0, W1) of the code only (W0 = 0, W1 = MW: the whole code).
+template <int GT, int MW, int W0 = 0, int W1 = MW>
 __device__ __forceinline__ typename vecf<GT>::type key_inner(const uint32_t (&w)[MW], const float* lut) {
   using V = typename vecf<GT>::type;
   const V* lutv = reinterpret_cast<const V*>(lut);
   V a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;         // four chains: adds do not wait on each other
 #pragma unroll
-  for (int wi = 0; wi < MW; ++wi) {
+  for (int wi = W0; wi < W1; ++wi) {
     a0 += lutv[(wi * 4 + 0) * 256 + (w[wi] & 255u)];
     a1 += lutv[(wi * 4 + 1) * 256 + ((w[wi] >> 8) & 255u)];
     a2 += lutv[(wi * 4 + 2) * 256 + ((w[wi] >> 16) & 255u)];

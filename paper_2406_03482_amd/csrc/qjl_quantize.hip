@@ -32,6 +32,10 @@ template <> struct mma<f16_t> {
   }
 };
 
+template <typename T> __device__ __forceinline__ float elem_to_float(uint16_t x);
+template <> __device__ __forceinline__ float elem_to_float<bf16_t>(uint16_t x) { return bf16_bits_to_float(x); }
+template <> __device__ __forceinline__ float elem_to_float<f16_t>(uint16_t x) { return f16_bits_to_float(x); }
+
 constexpr int kTok = 64;        // keys per tile: two N = 32 MFMA sub-tiles
 constexpr int kRowU4 = 17;      // LDS row pitch in 16-byte units: 256 B of key + 16 B pad
 
@@ -69,12 +73,31 @@ template <> __device__ __forceinline__ float sumsq8<f16_t>(const uint4& u) {
 //   HBM -> registers (issued one tile ahead) -> norm + LDS (padded rows)
 //   LDS -> MFMA B operands, S from registers, accumulators -> bits in registers
 //   bits -> LDS -> HBM as whole rows (16 bytes per lane, contiguous)
-template <typename T, int PPW>
+//
+// The rows are cut into segments (blockIdx.z): one segment holding every row when
+// all keys share one sketch, or one segment per (batch, kv head) when every head
+// has a sketch of its own (seg_stride elements apart).  DUAL (Section 4.1,
+// outlier channels): the code is that of a stacked sketch whose rows already
+// exclude / keep only the head's `count` outlier channels, and two norms are
+// stored: of the key without those channels and of those channels alone.
+template <typename T, int PPW, bool DUAL>
 __global__ void __launch_bounds__(256, 2)
-quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S,
-                     uint32_t* __restrict__ bits, uint16_t* __restrict__ norms, long rows, int m,
-                     int num_tiles) {
+quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S, size_t seg_stride,
+                     uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
+                     uint16_t* __restrict__ norms_out, const int32_t* __restrict__ channels, int count,
+                     long rows, int m, int num_tiles, int seg0) {
   using frag = typename mma<T>::frag;
+  {
+    const size_t seg = (size_t)seg0 + blockIdx.z;
+    K += seg * (size_t)rows * 128;
+    S += seg * seg_stride;
+    bits += seg * (size_t)rows * (size_t)(m >> 5);
+    norms += seg * (size_t)rows;
+    if constexpr (DUAL) {
+      norms_out += seg * (size_t)rows;
+      channels += seg * (size_t)count;
+    }
+  }
   constexpr int NA = PPW / 32;            // 32x32 MFMA tiles per wave along the projections
   constexpr int WPT = 4 * PPW / 32;       // code words per key written by this workgroup
   __shared__ uint4 kbuf[2][kTok * kRowU4];
@@ -158,6 +181,23 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     const int next = tile + gridDim.x;
     const bool has_next = next < num_tiles;
     if (has_next) load_tile(next);
+    // the tile's norms: its squared norms and its keys have been in LDS since the
+    // previous iteration's barrier and stay there until this iteration's barrier
+    if (blockIdx.y == 0 && wave == 3) {               // one wave, one key per lane: a single square root
+      const long trow = (long)tile * kTok + lane;
+      float sq_all = nsq[buf][lane];
+      if constexpr (DUAL) {
+        const uint16_t* krow = reinterpret_cast<const uint16_t*>(kbuf[buf]) + lane * (kRowU4 * 8);
+        float sq_out = 0.f;
+        for (int t = 0; t < count; ++t) {
+          const float x = elem_to_float<T>(krow[min(max(channels[t], 0), 127)]);
+          sq_out = fmaf(x, x, sq_out);
+        }
+        if (trow < rows) norms_out[trow] = float_to_f16_bits(sqrtf(sq_out));
+        sq_all = fmaxf(sq_all - sq_out, 0.f);
+      }
+      if (trow < rows) norms[trow] = float_to_f16_bits(sqrtf(sq_all));
+    }
 
     // ---- MFMA phase.  The tile's work is cut into NU units of two accumulator
     // chains (8 MFMAs each).  While unit u accumulates, the sign bits of unit
@@ -247,27 +287,28 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
         *reinterpret_cast<uint4*>(tb0 + off) = obuf[buf][tid];
       }
     }
-    if (blockIdx.y == 0 && wave == 3) {               // one wave, one key per lane: a single square root
-      const uint16_t nu = float_to_f16_bits(sqrtf(nsq[buf][lane]));
-      if (full || trow0 + lane < rows) (norms + trow0)[lane] = nu;
-    }
   }
 }
 
 // ---------------------------------------------------------------- generic fp32-FMA path
 constexpr int kGenTok = 8;
 
-template <typename T>
+template <typename T, bool DUAL>
 __global__ void __launch_bounds__(256)
-quantize_generic_kernel(const void* __restrict__ K, const void* __restrict__ S,
-                        uint32_t* __restrict__ bits, uint16_t* __restrict__ norms, long rows, int d,
-                        int m) {
+quantize_generic_kernel(const void* __restrict__ K, const void* __restrict__ S, size_t seg_stride,
+                        uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
+                        uint16_t* __restrict__ norms_out, const int32_t* __restrict__ channels, int count,
+                        long rows, int d, int m, int seg0) {
   extern __shared__ float4 smem4[];
   float* kf = reinterpret_cast<float*>(smem4);      // [kGenTok][d]
   const int tid = threadIdx.x;
+  const size_t seg = (size_t)seg0 + blockIdx.y;
+  const size_t k0 = seg * (size_t)rows * d;          // first element of the segment's keys
+  const size_t s0 = seg * seg_stride;
+  const size_t r0 = seg * (size_t)rows;
   const long row0 = (long)blockIdx.x * kGenTok;
   const int ntok = (int)min((long)kGenTok, rows - row0);
-  for (int e = tid; e < ntok * d; e += 256) kf[e] = load1<T>(K, (size_t)row0 * d + e);
+  for (int e = tid; e < ntok * d; e += 256) kf[e] = load1<T>(K, k0 + (size_t)row0 * d + e);
   __syncthreads();
   const int mw = m >> 5;
   for (int idx = tid; idx < ntok * mw; idx += 256) {
@@ -275,69 +316,108 @@ quantize_generic_kernel(const void* __restrict__ K, const void* __restrict__ S,
     const float* kr = kf + tok * d;
     uint32_t word = 0;
     for (int i = 0; i < 32; ++i) {
-      const size_t srow = (size_t)(wd * 32 + i) * d;
+      const size_t srow = s0 + (size_t)(wd * 32 + i) * d;
       float acc = 0.f;
       for (int t = 0; t < d; ++t) acc = fmaf(load1<T>(S, srow + t), kr[t], acc);
       word |= (acc >= 0.f ? 1u : 0u) << i;
     }
-    bits[(size_t)(row0 + tok) * mw + wd] = word;
+    bits[(r0 + row0 + tok) * mw + wd] = word;
   }
   if (tid < ntok) {
     const float* kr = kf + tid * d;
     float ss = 0.f;
     for (int t = 0; t < d; ++t) ss = fmaf(kr[t], kr[t], ss);
-    norms[row0 + tid] = float_to_f16_bits(sqrtf(ss));
+    if constexpr (DUAL) {
+      float so = 0.f;
+      for (int t = 0; t < count; ++t) {
+        const float x = kr[min(max(channels[seg * (size_t)count + t], 0), d - 1)];
+        so = fmaf(x, x, so);
+      }
+      norms_out[r0 + row0 + tid] = float_to_f16_bits(sqrtf(so));
+      ss = fmaxf(ss - so, 0.f);
+    }
+    norms[r0 + row0 + tid] = float_to_f16_bits(sqrtf(ss));
   }
 }
 
-template <typename T, int PPW>
-int launch_mfma(const void* K, const void* S, uint8_t* bits, uint16_t* norms, long rows, int m,
-                hipStream_t st) {
-  const long tiles = (rows + kTok - 1) / kTok;
+struct quant_io {
+  const void* K; const void* S; size_t seg_stride;      // seg_stride = 0: one sketch for all rows
+  uint8_t* bits; uint16_t* norms; uint16_t* norms_out;  // norms_out / channels: outlier split only
+  const int32_t* channels; int count;
+  long segments; long rows;                             // rows per segment
+  int d, m;                                             // m = all code bits of a key
+};
+
+template <typename T, int PPW, bool DUAL>
+int launch_mfma(const quant_io& q, hipStream_t st) {
+  const long tiles = (q.rows + kTok - 1) / kTok;
   if (tiles > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
-  long gx = 2L * device_cu_count();       // two resident workgroups per CU, each loops over tiles
+  // about two resident workgroups per CU in total, each looping over tiles of its segment
+  long gx = (2L * device_cu_count() + q.segments - 1) / q.segments;
   if (gx > tiles) gx = tiles;
-  dim3 grid((unsigned)gx, (unsigned)(m / (4 * PPW)));
-  hipLaunchKernelGGL((quantize_mfma_kernel<T, PPW>), grid, dim3(256), 0, st,
-                     static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(S),
-                     reinterpret_cast<uint32_t*>(bits), norms, rows, m, (int)tiles);
+  for (long s0 = 0; s0 < q.segments; s0 += 65535) {
+    const long nz = q.segments - s0 < 65535 ? q.segments - s0 : 65535;
+    dim3 grid((unsigned)gx, (unsigned)(q.m / (4 * PPW)), (unsigned)nz);
+    hipLaunchKernelGGL((quantize_mfma_kernel<T, PPW, DUAL>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(q.K), static_cast<const uint16_t*>(q.S), q.seg_stride,
+                       reinterpret_cast<uint32_t*>(q.bits), q.norms, q.norms_out, q.channels, q.count,
+                       q.rows, q.m, (int)tiles, (int)s0);
+  }
   return launch_status();
 }
 
-template <typename T>
-int launch_mfma_m(const void* K, const void* S, uint8_t* bits, uint16_t* norms, long rows, int m,
-                  hipStream_t st) {
-  if (m % 512 == 0) return launch_mfma<T, 128>(K, S, bits, norms, rows, m, st);
-  if (m % 256 == 0) return launch_mfma<T, 64>(K, S, bits, norms, rows, m, st);
-  return launch_mfma<T, 32>(K, S, bits, norms, rows, m, st);
+template <typename T, bool DUAL>
+int launch_mfma_m(const quant_io& q, hipStream_t st) {
+  if (q.m % 512 == 0) return launch_mfma<T, 128, DUAL>(q, st);
+  if (q.m % 256 == 0) return launch_mfma<T, 64, DUAL>(q, st);
+  return launch_mfma<T, 32, DUAL>(q, st);
 }
 
-template <typename T>
-int launch_generic(const void* K, const void* S, uint8_t* bits, uint16_t* norms, long rows, int d,
-                   int m, hipStream_t st) {
-  const long blocks = (rows + kGenTok - 1) / kGenTok;
+template <typename T, bool DUAL>
+int launch_generic(const quant_io& q, hipStream_t st) {
+  const long blocks = (q.rows + kGenTok - 1) / kGenTok;
   if (blocks > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(quantize_generic_kernel<T>, dim3((unsigned)blocks), dim3(256),
-                     (size_t)kGenTok * d * sizeof(float), st, K, S,
-                     reinterpret_cast<uint32_t*>(bits), norms, rows, d, m);
+  for (long s0 = 0; s0 < q.segments; s0 += 65535) {
+    const long ny = q.segments - s0 < 65535 ? q.segments - s0 : 65535;
+    hipLaunchKernelGGL((quantize_generic_kernel<T, DUAL>), dim3((unsigned)blocks, (unsigned)ny), dim3(256),
+                       (size_t)kGenTok * q.d * sizeof(float), st, q.K, q.S, q.seg_stride,
+                       reinterpret_cast<uint32_t*>(q.bits), q.norms, q.norms_out, q.channels, q.count,
+                       q.rows, q.d, q.m, (int)s0);
+  }
   return launch_status();
+}
+
+template <bool DUAL>
+int launch_any(const quant_io& q, int dtype, hipStream_t st) {
+  const bool mfma_ok = q.d == 128 && q.m % 128 == 0 && dtype != QJL_F32;
+  if (mfma_ok) {
+    if (dtype == QJL_BF16) return launch_mfma_m<bf16_t, DUAL>(q, st);
+    return launch_mfma_m<f16_t, DUAL>(q, st);
+  }
+  switch (dtype) {
+    case QJL_F32: return launch_generic<f32_t, DUAL>(q, st);
+    case QJL_F16: return launch_generic<f16_t, DUAL>(q, st);
+    default: return launch_generic<bf16_t, DUAL>(q, st);
+  }
 }
 
 }  // namespace
 
 int launch_quantize(const qjl_shape& sh, const void* K, const void* S, uint8_t* bits,
                     uint16_t* norms, hipStream_t st) {
-  const long rows = (long)sh.batch * sh.kv_heads * sh.n;
-  const bool mfma_ok = sh.d == 128 && sh.m % 128 == 0 && sh.dtype != QJL_F32;
-  if (mfma_ok) {
-    if (sh.dtype == QJL_BF16) return launch_mfma_m<bf16_t>(K, S, bits, norms, rows, sh.m, st);
-    return launch_mfma_m<f16_t>(K, S, bits, norms, rows, sh.m, st);
-  }
-  switch (sh.dtype) {
-    case QJL_F32: return launch_generic<f32_t>(K, S, bits, norms, rows, sh.d, sh.m, st);
-    case QJL_F16: return launch_generic<f16_t>(K, S, bits, norms, rows, sh.d, sh.m, st);
-    default: return launch_generic<bf16_t>(K, S, bits, norms, rows, sh.d, sh.m, st);
-  }
+  quant_io q{K, S, 0, bits, norms, nullptr, nullptr, 0, 1, (long)sh.batch * sh.kv_heads * sh.n, sh.d, sh.m};
+  return launch_any<false>(q, sh.dtype, st);
+}
+
+// Two-part codes (Section 4.1): S_dual holds one stacked sketch [sh.m + m_out, d] per
+// (batch, kv head); channels [B,Hkv,count] lists that head's outlier channels.
+int launch_quantize_dual(const qjl_shape& sh, int m_out, const void* K, const void* S_dual,
+                         const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                         uint16_t* norms_out, hipStream_t st) {
+  const int mt = sh.m + m_out;
+  quant_io q{K, S_dual, (size_t)mt * sh.d, bits, norms_in, norms_out, channels, count,
+             (long)sh.batch * sh.kv_heads, (long)sh.n, sh.d, mt};
+  return launch_any<true>(q, sh.dtype, st);
 }
 
 }  // namespace qjl

@@ -34,6 +34,7 @@ class Workload:
     data_seed: int
     sketch_seed: int
     outliers: int = 4
+    m_out: int = 0          # > 0: outlier channels get a second sketch of m_out rows (m is the inlier sketch)
 
     @property
     def key_heads(self) -> int:
@@ -55,6 +56,10 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     # Llama-3-8B-shaped grouped-query decode, two shapes
     Workload("c5a_llama3_8b_gqa_b1_128k", 1, 32, 8, 131072, 128, 256, torch.bfloat16, _RS, 1005, 5),
     Workload("c5b_llama3_8b_gqa_b16_8k", 16, 32, 8, 8192, 128, 256, torch.bfloat16, _RS, 1006, 5),
+    # the same shapes with the outlier channels quantized separately: 256 + 128 bits = 3 bits per coordinate
+    Workload("c2d_llama2_7b_decode_4k_dual", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, m_out=128),
+    Workload("c3d_long_context_b4_32k_dual", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, m_out=128),
+    Workload("c4d_prefill_quantize_64k_dual", 1, 32, 32, 65536, 128, 256, torch.bfloat16, _RS, 1004, 4, m_out=128),
 ]}
 
 

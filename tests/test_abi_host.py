@@ -30,10 +30,11 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(L):
     names = _declared_symbols()
-    assert names == ["qjl_decode_attention", "qjl_decode_attention_timed",
-                     "qjl_decode_workspace_bytes", "qjl_make_sketch",
-                     "qjl_project_query", "qjl_quantize_keys", "qjl_scores", "qjl_status_string",
-                     "qjl_version"]
+    assert names == ["qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
+                     "qjl_decode_dual_workspace_bytes", "qjl_decode_workspace_bytes",
+                     "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_outlier_workspace_bytes",
+                     "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_scores",
+                     "qjl_select_outliers", "qjl_status_string", "qjl_version"]
     for n in names:
         assert hasattr(L, n), n
 
@@ -130,3 +131,31 @@ def test_python_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         qjl.qjl_project_query(torch.zeros(1, 1, 128), torch.zeros(256, 128))
+
+
+def test_dual_entry_points_validate_on_the_host(L):
+    """Outlier-channel calls: bad arguments are turned into status codes before any launch."""
+    sh = QJLShape(1, 4, 2, 100, 128, 256, 2, 1.0)
+    ok = ctypes.c_void_p(0x1000)                     # aligned, never dereferenced: every call below fails earlier
+    vp = ctypes.c_void_p
+    L.qjl_outlier_workspace_bytes.restype = ctypes.c_size_t
+    L.qjl_decode_dual_workspace_bytes.restype = ctypes.c_size_t
+    assert L.qjl_outlier_workspace_bytes(ctypes.byref(sh)) == 1 * 2 * 1 * 128 * 4
+    assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(sh), 128) > 0
+    assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(sh), 64) == 0       # unsupported split
+    bad = QJLShape(1, 4, 2, 100, 128, 512, 2, 1.0)
+    assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(bad), 128) == 0
+    # count out of range / null pointers
+    assert L.qjl_select_outliers(ctypes.byref(sh), ok, 0, ok, ok, ctypes.c_size_t(1 << 20), None) == INVALID
+    assert L.qjl_select_outliers(ctypes.byref(sh), ok, 17, ok, ok, ctypes.c_size_t(1 << 20), None) == INVALID
+    assert L.qjl_select_outliers(ctypes.byref(sh), ok, 4, ok, ok, ctypes.c_size_t(16), None) == WORKSPACE
+    assert L.qjl_select_outliers(ctypes.byref(sh), vp(None), 4, ok, ok, ctypes.c_size_t(1 << 20), None) == INVALID
+    assert L.qjl_make_dual_sketch(ctypes.byref(sh), 0, ok, ok, ok, 4, ok, None) == INVALID
+    assert L.qjl_make_dual_sketch(ctypes.byref(sh), 128, ok, vp(None), ok, 4, ok, None) == INVALID
+    assert L.qjl_quantize_keys_dual(ctypes.byref(sh), 128, ok, ok, vp(None), 4, ok, ok, ok, None) == INVALID
+    odd = QJLShape(1, 4, 2, 100, 128, 250, 2, 1.0)
+    assert L.qjl_quantize_keys_dual(ctypes.byref(odd), 128, ok, ok, ok, 4, ok, ok, ok, None) == UNSUPPORTED
+    assert L.qjl_decode_attention_dual(ctypes.byref(sh), 128, ok, ok, ok, ok, ok, ok, ok, vp(None),
+                                       ctypes.c_size_t(0), None) == WORKSPACE
+    assert L.qjl_decode_attention_dual(ctypes.byref(sh), 64, ok, ok, ok, ok, ok, ok, ok, ok,
+                                       ctypes.c_size_t(1 << 30), None) == UNSUPPORTED

@@ -1,0 +1,302 @@
+"""GPU-vs-oracle parity of the outlier/inlier path (Section 4.1), through the C ABI.
+
+Same bars as the single-sketch path: channel lists and stacked sketches exact,
+code bits exact outside the near-zero band |(S k)_i| < 1e-5 ||s_i|| ||k_part||,
+norms 1e-3 relative, attention outputs 2e-3 absolute.  Each stage consumes the
+oracle's output of the stage before it; only the end-to-end test chains the GPU
+stages, and it is compared with the oracle's own chain.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_03482_amd as qjl
+from paper_2406_03482_amd import inputs
+from oracle import qjl_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+DT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    assert os.path.exists(qjl.lib_path()), "libqjl.so must be built before the GPU tests run"
+    qjl.lib()
+
+
+def _dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def _stacked_sketch_numpy(S_in, S_out, channels):
+    """[B,Hkv,m+m_out,d] from the definition (numpy masks), in the storage dtype of S_in."""
+    B, H, _ = channels.shape
+    d = S_in.shape[1]
+    out = torch.zeros((B, H, S_in.shape[0] + S_out.shape[0], d), dtype=S_in.dtype)
+    si, so = S_in.cpu(), S_out.cpu()
+    for b in range(B):
+        for h in range(H):
+            mask = torch.zeros(d, dtype=torch.bool)
+            mask[torch.from_numpy(channels[b, h].astype(np.int64))] = True
+            out[b, h, : S_in.shape[0]] = torch.where(mask, torch.zeros_like(si), si)
+            out[b, h, S_in.shape[0]:] = torch.where(mask, so, torch.zeros_like(so))
+    return out
+
+
+# ------------------------------------------------------------------ channel selection
+@pytest.mark.parametrize("dt,B,Hkv,n,d,count", [
+    ("bf16", 2, 3, 300, 128, 4), ("bf16", 1, 2, 5000, 128, 4), ("f16", 1, 2, 2049, 128, 1),
+    ("f32", 1, 1, 1024, 128, 8), ("f32", 2, 2, 77, 48, 3), ("bf16", 1, 1, 1, 128, 4),
+])
+def test_select_outliers_parity(dt, B, Hkv, n, d, count):
+    say(f"[select] dt={dt} B={B} Hkv={Hkv} n={n} d={d} count={count}")
+    K = inputs.make_keys(B, Hkv, n, d, DT[dt], 300 + n, DEV, outliers=4)
+    got = qjl.qjl_select_outliers(K, count).cpu().numpy()
+    K64 = inputs.to_f64(K)
+    ref = orc.select_outlier_channels(K64, count)
+    mean_abs = np.abs(K64).mean(axis=2)
+    exact = True
+    for b in range(B):
+        for h in range(Hkv):
+            g, r = got[b, h].tolist(), ref[b, h].tolist()
+            assert len(set(g)) == count and all(0 <= t < d for t in g)
+            if g != r:
+                exact = False
+                # the list is unique only up to ties: a different order/choice is valid iff the means agree
+                # to fp32 summation accuracy at every position where the lists differ
+                for a, c in zip(g, r):
+                    assert abs(mean_abs[b, h, a] - mean_abs[b, h, c]) <= 2e-6 * mean_abs[b, h, c], (b, h, g, r)
+    say(f"  lists identical to the oracle's: {exact}")
+    if n >= 64 and count <= 4:
+        assert exact                                  # four x15 channels: nothing is close
+        planted = inputs.outlier_channels(Hkv, d, 4, 300 + n).numpy()
+        for b in range(B):
+            for h in range(Hkv):
+                assert set(got[b, h].tolist()) <= set(planted[h].tolist())
+    again = qjl.qjl_select_outliers(K, count).cpu().numpy()
+    assert np.array_equal(got, again)                 # deterministic
+
+
+# ------------------------------------------------------------------ stacked sketch
+@pytest.mark.parametrize("dt,B,Hkv,m,m_out,d,count", [
+    ("bf16", 2, 3, 256, 128, 128, 4), ("f16", 1, 1, 128, 128, 128, 1), ("f32", 1, 2, 64, 32, 48, 3),
+    ("bf16", 1, 1, 256, 128, 128, 0),
+])
+def test_make_dual_sketch_is_exact(dt, B, Hkv, m, m_out, d, count):
+    say(f"[dual sketch] dt={dt} B={B} Hkv={Hkv} m={m}+{m_out} d={d} count={count}")
+    S_in = qjl.qjl_make_sketch(21, m, d, DT[dt], DEV)
+    S_out = qjl.qjl_make_sketch(22, m_out, d, DT[dt], DEV)
+    rng = np.random.default_rng(5)
+    ch = np.stack([np.stack([rng.permutation(d)[:count] for _ in range(Hkv)]) for _ in range(B)]).reshape(B, Hkv, count)
+    got = qjl.qjl_make_dual_sketch(S_in, S_out, _dev_i32(ch)).cpu()
+    want = _stacked_sketch_numpy(S_in, S_out, ch)
+    assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+    # definition check in float64: S_dual k = [S_in k_in ; S_out k_out]
+    k = np.random.default_rng(6).standard_normal(d)
+    for b in range(B):
+        for h in range(Hkv):
+            mask = np.zeros(d); mask[ch[b, h]] = 1.0
+            sd = inputs.to_f64(got[b, h])
+            assert np.array_equal(sd[:m] @ k, inputs.to_f64(S_in) @ (k * (1 - mask)))
+            assert np.array_equal(sd[m:] @ k, inputs.to_f64(S_out) @ (k * mask))
+
+
+# ------------------------------------------------------------------ quantize
+def _dual_bits_report(bits_gpu, K64, S_in64, S_out64, ch):
+    ref_bits, nu_in, nu_out, P_in, P_out = orc.quantize_keys_dual(K64, S_in64, S_out64, ch)
+    m_in, m_out = S_in64.shape[0], S_out64.shape[0]
+    K_in, K_out = orc.split_channels(K64, ch)
+    bad = flips = inband = 0
+    for lo, hi, m, P, S64, Kp in ((0, m_in // 8, m_in, P_in, S_in64, K_in), (m_in // 8, (m_in + m_out) // 8, m_out, P_out, S_out64, K_out)):
+        diff = orc.unpack_signs(bits_gpu[..., lo:hi], m) != orc.unpack_signs(ref_bits[..., lo:hi], m)
+        # band relative to the norms of what each instance actually sees: the masked sketch rows and the key part
+        B, H = K64.shape[:2]
+        band = np.zeros_like(diff)
+        for b in range(B):
+            for h in range(H):
+                mask = np.zeros(K64.shape[-1]); mask[ch[b, h]] = 1.0
+                Sm = S64 * (mask if S64 is S_out64 else (1 - mask))
+                band[b, h] = np.abs(P[b, h]) < 1e-5 * np.linalg.norm(Sm, axis=1) * np.linalg.norm(Kp[b, h], axis=-1, keepdims=True)
+        bad += int((diff & ~band).sum()); flips += int((diff & band).sum()); inband += int(band.sum())
+    return bad, flips, inband, nu_in, nu_out
+
+
+def _assert_norms(got16, ref64):
+    got = got16.astype(np.float64)
+    assert np.all(np.abs(got - ref64) <= 1e-3 * ref64 + 1e-30), float(np.max(np.abs(got - ref64) / (ref64 + 1e-30)))
+
+
+@pytest.mark.parametrize("dt,B,Hkv,n,d,m,m_out,count", [
+    ("bf16", 2, 2, 333, 128, 256, 128, 4),       # 384-bit codes, ragged tiles, several heads
+    ("bf16", 1, 3, 64, 128, 128, 128, 4),        # 256-bit codes
+    ("f16", 1, 2, 1000, 128, 256, 128, 2),
+    ("bf16", 1, 1, 4096, 128, 256, 128, 4),
+    ("f32", 1, 2, 100, 128, 256, 128, 4),        # fp32 keys: FMA path
+    ("f32", 2, 1, 37, 48, 64, 32, 3),            # odd shape, FMA path
+])
+def test_quantize_keys_dual_parity(dt, B, Hkv, n, d, m, m_out, count):
+    say(f"[quantize dual] dt={dt} B={B} Hkv={Hkv} n={n} d={d} m={m}+{m_out} count={count}")
+    K = inputs.make_keys(B, Hkv, n, d, DT[dt], 500 + n, DEV, outliers=4)
+    S_in = qjl.qjl_make_sketch(31, m, d, DT[dt], DEV)
+    S_out = qjl.qjl_make_sketch(32, m_out, d, DT[dt], DEV)
+    K64, S_in64, S_out64 = inputs.to_f64(K), inputs.to_f64(S_in), inputs.to_f64(S_out)
+    ch = orc.select_outlier_channels(K64, count)
+    S_dual = _stacked_sketch_numpy(S_in, S_out, ch).to(DEV)
+    bits, nu_in, nu_out = qjl.qjl_quantize_keys_dual(K, S_dual, _dev_i32(ch), m_out)
+    torch.cuda.synchronize()
+    bad, flips, inband, ref_in, ref_out = _dual_bits_report(bits.cpu().numpy(), K64, S_in64, S_out64, ch)
+    say(f"  bits: {bad} mismatches outside the band, {flips} flips among {inband} near-zero entries of {B * Hkv * n * (m + m_out)}")
+    assert bad == 0
+    K_in, K_out = orc.split_channels(K64, ch)
+    _assert_norms(nu_in.cpu().numpy(), np.linalg.norm(K_in, axis=-1))
+    _assert_norms(nu_out.cpu().numpy(), np.linalg.norm(K_out, axis=-1))
+    say(f"  norms identical to the oracle's binary16: in {float(np.mean(nu_in.cpu().numpy() == ref_in)):.4f} out {float(np.mean(nu_out.cpu().numpy() == ref_out)):.4f}")
+    b2, i2, o2 = qjl.qjl_quantize_keys_dual(K, S_dual, _dev_i32(ch), m_out)
+    assert torch.equal(bits, b2) and torch.equal(nu_in, i2) and torch.equal(nu_out, o2)
+
+
+def test_quantize_dual_zero_keys():
+    """All-zero keys: every projection is +0 -> all bits 1, both norms 0; a key that is zero outside its outlier
+    channels has a zero inlier norm."""
+    B, Hkv, n, d, m, m_out = 1, 1, 70, 128, 256, 128
+    K = torch.zeros((B, Hkv, n, d), dtype=torch.bfloat16, device=DEV)
+    K[0, 0, 5:, 17] = 3.0
+    K[0, 0, 5:, 90] = -4.0
+    ch = np.array([[[17, 90]]])
+    S_in = qjl.qjl_make_sketch(1, m, d, torch.bfloat16, DEV)
+    S_out = qjl.qjl_make_sketch(2, m_out, d, torch.bfloat16, DEV)
+    S_dual = _stacked_sketch_numpy(S_in, S_out, ch).to(DEV)
+    bits, nu_in, nu_out = qjl.qjl_quantize_keys_dual(K, S_dual, _dev_i32(ch), m_out)
+    bits, nu_in, nu_out = bits.cpu().numpy(), nu_in.cpu().numpy(), nu_out.cpu().numpy()
+    ref_bits, ref_in, ref_out, _, _ = orc.quantize_keys_dual(inputs.to_f64(K), inputs.to_f64(S_in), inputs.to_f64(S_out), ch)
+    assert np.all(bits[0, 0, :5] == 0xFF) and np.all(bits[0, 0, :, : m // 8] == 0xFF)
+    assert np.array_equal(bits, ref_bits)
+    assert not nu_in.any() and np.array_equal(nu_out, ref_out) and np.all(nu_out[0, 0, 5:] == 5.0)
+
+
+# ------------------------------------------------------------------ decode
+DUAL_DECODE_CASES = [
+    # dtype, B, Hq, Hkv, n, m, m_out, scale
+    ("bf16", 2, 4, 4, 1000, 256, 128, 0.0884),    # MHA, 384-bit codes
+    ("bf16", 1, 8, 2, 1500, 128, 128, 0.0884),    # GQA x4 on 256-bit codes
+    ("bf16", 1, 8, 2, 700, 256, 128, 0.0884),     # GQA x4 on 384-bit codes -> two heads at a time
+    ("bf16", 1, 6, 3, 333, 256, 128, 1.0),        # GQA x2, paper-literal scale
+    ("f16", 1, 3, 1, 260, 256, 128, 0.0884),      # GQA x3 -> one head at a time
+    ("f32", 1, 2, 2, 300, 128, 128, 0.0884),
+    ("bf16", 1, 2, 2, 1, 256, 128, 1.0),          # n = 1
+    ("bf16", 1, 1, 1, 65, 256, 128, 0.0884),
+    ("bf16", 1, 2, 1, 20000, 256, 128, 0.0884),   # many chunks
+]
+
+
+@pytest.mark.parametrize("dt,B,Hq,Hkv,n,m,m_out,scale", DUAL_DECODE_CASES)
+def test_decode_attention_dual_parity(dt, B, Hq, Hkv, n, m, m_out, scale):
+    say(f"[decode dual] dt={dt} B={B} Hq={Hq} Hkv={Hkv} n={n} m={m}+{m_out} scale={scale}")
+    d = 128
+    K = inputs.make_keys(B, Hkv, n, d, DT[dt], 600 + n, DEV, outliers=4)
+    Q = inputs.make_normal((B, Hq, d), DT[dt], 61, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), DT[dt], 62, DEV)
+    S_in = qjl.qjl_make_sketch(41, m, d, DT[dt], DEV)
+    S_out = qjl.qjl_make_sketch(42, m_out, d, DT[dt], DEV)
+    K64, S_in64, S_out64 = inputs.to_f64(K), inputs.to_f64(S_in), inputs.to_f64(S_out)
+    ch = orc.select_outlier_channels(K64, 4)
+    bits, nu_in, nu_out, _, _ = orc.quantize_keys_dual(K64, S_in64, S_out64, ch)      # the oracle's cache
+    ref = orc.decode_attention_dual(inputs.to_f64(Q), S_in64, S_out64, ch, bits, nu_in, nu_out, inputs.to_f64(V), scale)
+    S_dual = _stacked_sketch_numpy(S_in, S_out, ch).to(DEV)
+    args = (Q, S_dual, torch.from_numpy(bits).to(DEV), torch.from_numpy(nu_in).to(DEV), torch.from_numpy(nu_out).to(DEV), V, m_out, scale)
+    out = qjl.qjl_decode_attention_dual(*args)
+    err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref)))
+    say(f"  max abs error {err:.3g}")
+    assert err <= 2e-3
+    assert torch.equal(out, qjl.qjl_decode_attention_dual(*args))
+
+
+def test_dual_pipeline_end_to_end_and_gain_over_one_sketch():
+    """select -> stacked sketch -> quantize -> decode, all on the GPU, against the oracle's own chain; and
+    the point of the exercise: at equal bits per key the split estimate is closer to exact attention."""
+    B, Hq, Hkv, n, d, m, m_out, scale = 1, 4, 4, 2048, 128, 256, 128, 0.0884
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 77, DEV, outliers=4)
+    Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 78, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 79, DEV)
+    S_in = qjl.qjl_make_sketch(51, m, d, torch.bfloat16, DEV)
+    S_out = qjl.qjl_make_sketch(52, m_out, d, torch.bfloat16, DEV)
+    ch_d = qjl.qjl_select_outliers(K, 4)
+    S_dual = qjl.qjl_make_dual_sketch(S_in, S_out, ch_d)
+    bits, nu_in, nu_out = qjl.qjl_quantize_keys_dual(K, S_dual, ch_d, m_out)
+    out = qjl.qjl_decode_attention_dual(Q, S_dual, bits, nu_in, nu_out, V, m_out, scale).cpu().numpy().astype(np.float64)
+    K64, Q64, V64 = inputs.to_f64(K), inputs.to_f64(Q), inputs.to_f64(V)
+    S_in64, S_out64 = inputs.to_f64(S_in), inputs.to_f64(S_out)
+    ch = orc.select_outlier_channels(K64, 4)
+    assert np.array_equal(ch_d.cpu().numpy(), ch)
+    rb, ri, ro, _, _ = orc.quantize_keys_dual(K64, S_in64, S_out64, ch)
+    ref = orc.decode_attention_dual(Q64, S_in64, S_out64, ch, rb, ri, ro, V64, scale)
+    # the GPU's code may differ from the oracle's in near-zero entries; their effect on the output is far below the bar
+    err = float(np.max(np.abs(out - ref)))
+    say(f"[dual chain] max abs error vs oracle chain {err:.3g}")
+    assert err <= 2e-3
+    # exact attention and a single 384-bit sketch, both by the oracle
+    exact = orc.attention_from_scores(scale * np.einsum("bhd,bhnd->bhn", Q64, K64), V64)
+    S1 = inputs.to_f64(qjl.qjl_make_sketch(53, m + m_out, d, torch.bfloat16, DEV))
+    b1, n1, _ = orc.quantize_keys(K64, S1)
+    single = orc.decode_attention(Q64, S1, b1, n1, V64, scale)
+    e_dual = float(np.sqrt(np.mean((out - exact) ** 2)))
+    e_single = float(np.sqrt(np.mean((single - exact) ** 2)))
+    say(f"  rms error to exact attention: split {e_dual:.4f}, one sketch of the same size {e_single:.4f}")
+    assert e_dual < e_single
+
+
+@pytest.mark.parametrize("name,units", [("c2d_llama2_7b_decode_4k_dual", 8), ("c3d_long_context_b4_32k_dual", 3)])
+def test_full_size_dual_sampled(name, units):
+    """The benchmark's launch configuration at full size; the oracle checks sampled (batch, kv head) units:
+    their channels, code and norms against the GPU's, then (on the oracle's code) their attention outputs."""
+    w = inputs.WORKLOADS[name]
+    say(f"[full dual] {name}")
+    K, Q, V = inputs.make_workload_tensors(w, DEV)
+    S_in = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, DEV)
+    S_out = qjl.qjl_make_sketch(w.sketch_seed + 1000, w.m_out, w.d, w.dtype, DEV)
+    S_in64, S_out64, Q64 = inputs.to_f64(S_in), inputs.to_f64(S_out), inputs.to_f64(Q)
+    ch_d = qjl.qjl_select_outliers(K, 4)
+    S_dual = qjl.qjl_make_dual_sketch(S_in, S_out, ch_d)
+    bits_d, in_d, out_d = qjl.qjl_quantize_keys_dual(K, S_dual, ch_d, w.m_out)
+    rng = np.random.default_rng(w.data_seed)
+    picked = sorted(rng.choice(w.batch * w.kv_heads, size=units, replace=False).tolist())
+    refs = {}
+    tot_bad = tot_flip = 0
+    for u in picked:
+        b, g = divmod(u, w.kv_heads)
+        K64 = inputs.to_f64(K[b, g])[None, None]
+        ch = orc.select_outlier_channels(K64, 4)
+        assert np.array_equal(ch_d[b, g].cpu().numpy(), ch[0, 0])
+        bad, flips, _, ri, ro = _dual_bits_report(bits_d[b, g].cpu().numpy()[None, None], K64, S_in64, S_out64, ch)
+        tot_bad += bad; tot_flip += flips
+        K_in, K_out = orc.split_channels(K64, ch)
+        _assert_norms(in_d[b, g].cpu().numpy()[None, None], np.linalg.norm(K_in, axis=-1))
+        _assert_norms(out_d[b, g].cpu().numpy()[None, None], np.linalg.norm(K_out, axis=-1))
+        rb, _, _, _, _ = orc.quantize_keys_dual(K64, S_in64, S_out64, ch)
+        bits_d[b, g] = torch.from_numpy(rb[0, 0]).to(DEV)               # both sides use the oracle's cache
+        in_d[b, g] = torch.from_numpy(ri[0, 0]).to(DEV)
+        out_d[b, g] = torch.from_numpy(ro[0, 0]).to(DEV)
+        refs[(b, g)] = orc.decode_attention_dual(Q64[b:b + 1, g:g + 1], S_in64, S_out64, ch, rb, ri, ro,
+                                                 inputs.to_f64(V[b, g])[None, None], w.scale)[0]
+        say(f"  unit b={b} kv={g}: oracle done")
+    say(f"  quantize on sampled units: {tot_bad} outside band, {tot_flip} near-zero flips")
+    assert tot_bad == 0
+    del K
+    out = qjl.qjl_decode_attention_dual(Q, S_dual, bits_d, in_d, out_d, V, w.m_out, w.scale).cpu().numpy()
+    worst = 0.0
+    for (b, g), ref in refs.items():
+        worst = max(worst, float(np.max(np.abs(out[b, g:g + 1].astype(np.float64) - ref))))
+    say(f"  worst attention error over {len(refs)} heads: {worst:.3g}")
+    assert worst <= 2e-3 and np.all(np.isfinite(out))
+    vmax = V.float().amax(dim=2).cpu().numpy()
+    vmin = V.float().amin(dim=2).cpu().numpy()
+    assert np.all(out <= vmax + 1e-3) and np.all(out >= vmin - 1e-3)
