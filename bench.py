@@ -72,7 +72,7 @@ class HipEvents:
 
 def decode_bytes_per_key(w) -> int:
     """Algorithmic HBM bytes per (batch, kv head, token): code + norm + one row of V."""
-    return w.m // 8 + 2 + w.d * 2
+    return (w.m + w.m_out) // 8 + (4 if w.m_out else 2) + w.d * 2
 
 
 def load_traffic(name: str):
@@ -91,6 +91,17 @@ def prepare_decode(qjl, inputs, w, dev):
     import torch
     K, Q, V = inputs.make_workload_tensors(w, dev)
     S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    if w.m_out:                                     # outlier channels quantized separately (Section 4.1)
+        S_out = qjl.qjl_make_sketch(w.sketch_seed + 1000, w.m_out, w.d, w.dtype, dev)
+        ch = qjl.qjl_select_outliers(K, 4)
+        S = qjl.qjl_make_dual_sketch(S, S_out, ch)
+        bits, norms, norms_out = qjl.qjl_quantize_keys_dual(K, S, ch, w.m_out)
+        del K
+        ws = torch.empty((qjl.qjl_decode_dual_workspace_bytes(w.batch, w.q_heads, w.kv_heads, w.n, w.d, w.m,
+                                                              w.m_out, w.dtype),), dtype=torch.uint8, device=dev)
+        out = torch.empty((w.batch, w.q_heads, w.d), dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        return dict(Q=Q, S=S, bits=bits, norms=norms, norms_out=norms_out, V=V, ws=ws, out=out)
     bits, norms = qjl.qjl_quantize_keys(K, S)       # untimed: the cache already exists at decode time
     del K
     ws = torch.empty((qjl.qjl_decode_workspace_bytes(w.batch, w.q_heads, w.kv_heads, w.n, w.d, w.m, w.dtype),),
@@ -101,6 +112,10 @@ def prepare_decode(qjl, inputs, w, dev):
 
 
 def run_decode(qjl, t, w, events=None):
+    if w.m_out:
+        qjl.qjl_decode_attention_dual(t["Q"], t["S"], t["bits"], t["norms"], t["norms_out"], t["V"], w.m_out,
+                                      w.scale, out=t["out"], workspace=t["ws"], events=events)
+        return
     qjl.qjl_decode_attention(t["Q"], t["S"], t["bits"], t["norms"], t["V"], w.scale, out=t["out"],
                              workspace=t["ws"], events=events)
 
@@ -173,24 +188,33 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     import torch
     K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, dev, w.outliers)
     S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
-    bits = torch.empty((w.batch, w.kv_heads, w.n, w.m // 8), dtype=torch.uint8, device=dev)
+    mt = w.m + w.m_out
+    bits = torch.empty((w.batch, w.kv_heads, w.n, mt // 8), dtype=torch.uint8, device=dev)
     norms = torch.empty((w.batch, w.kv_heads, w.n), dtype=torch.float16, device=dev)
+    if w.m_out:      # timed: the quantizer itself; channel selection and the stacked sketch are one-off prompt-phase steps
+        S_out = qjl.qjl_make_sketch(w.sketch_seed + 1000, w.m_out, w.d, w.dtype, dev)
+        ch = qjl.qjl_select_outliers(K, 4)
+        S = qjl.qjl_make_dual_sketch(S, S_out, ch)
+        norms_out = torch.empty_like(norms)
+        call = lambda: qjl.qjl_quantize_keys_dual(K, S, ch, w.m_out, bits, norms, norms_out)
+    else:
+        call = lambda: qjl.qjl_quantize_keys(K, S, bits, norms)
     stream = torch.cuda.current_stream().cuda_stream
     for _ in range(warmup):
-        qjl.qjl_quantize_keys(K, S, bits, norms)
+        call()
     torch.cuda.synchronize()
     a, b = ev.create(), ev.create()
     ev.record(a, stream)
     for _ in range(steps):
-        qjl.qjl_quantize_keys(K, S, bits, norms)
+        call()
     ev.record(b, stream)
     ms = ev.elapsed_ms(a, b) / steps          # one kernel per call, back to back: events bracket the kernels
     ev.destroy(a)
     ev.destroy(b)
     rows = w.batch * w.kv_heads * w.n
-    flops = 2.0 * w.d * w.m * rows
+    flops = 2.0 * w.d * mt * rows
     achieved = flops / (ms * 1e-3) / 1e12
-    algo_bytes = rows * (w.d * 2 + w.m // 8 + 2)
+    algo_bytes = rows * (w.d * 2 + mt // 8 + (4 if w.m_out else 2))
     return {
         "workload": w.name,
         "metric": "prefill quantize tokens/s",
@@ -236,7 +260,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
-                    "metric is quoted on), c3, c5a, c5b (decode) or c4 (prefill quantize), for profiling single kernels; "
+                    "metric is quoted on), c3, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
+                    "quantized separately), for profiling single kernels; "
                     "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -272,7 +297,7 @@ def main() -> int:
         print(f"bench.py: unknown workload {args.workload!r}", file=sys.stderr)
         return 2
     w = inputs.WORKLOADS[names[args.workload]]
-    if args.workload == "c4":
+    if args.workload.startswith("c4"):
         head = bench_quantize(qjl, inputs, ev, w, dev, args.steps, args.warmup)
         head["ms_per_step_eager"] = head["ms_per_step"]
         r = {"graph_batch": 0}
@@ -286,7 +311,7 @@ def main() -> int:
     line = {
         "metric": head["metric"],
         "value": head["value"],
-        "unit": "tokens/s" if args.workload == "c4" else "keys/s",
+        "unit": "tokens/s" if args.workload.startswith("c4") else "keys/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -298,23 +323,25 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
-                   "context": w.n, "d": w.d, "m": w.m, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
+                   "context": w.n, "d": w.d, "m": w.m, "m_out": w.m_out, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
         "roofline": head["roofline"],
     }
 
     if not args.no_extra:
         extra = []
         for name, steps, warm in [("c3_long_context_b4_32k", 100, 20), ("c5a_llama3_8b_gqa_b1_128k", 200, 20),
-                                  ("c5b_llama3_8b_gqa_b16_8k", 200, 20)]:
+                                  ("c5b_llama3_8b_gqa_b16_8k", 200, 20), ("c2d_llama2_7b_decode_4k_dual", 400, 40),
+                                  ("c3d_long_context_b4_32k_dual", 100, 20)]:
             wx = inputs.WORKLOADS[name]
             tx = prepare_decode(qjl, inputs, wx, dev)
             extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm)))
             del tx
             torch.cuda.empty_cache()
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
+        extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 50, 5))
         line["other_workloads"] = extra
 
-    if not args.no_cpu and args.workload != "c4":
+    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out:
         line["cpu_baseline"] = cpu_baseline(inputs, w)
     else:
         line["cpu_baseline"] = None

@@ -207,12 +207,14 @@ size_t qjl_decode_dual_workspace_bytes(const qjl_shape* shape, int m_out);
  *                                  + norms_out[j]/m_out * <S_out q_out, outlier bits_j> )
  * then softmax and Eq. (1).  S_dual as written by qjl_make_dual_sketch.
  * Supported: d == 128, m in {128, 256}, m_out == 128.  Workspace rules as for
- * qjl_decode_attention.
+ * qjl_decode_attention; event_before / event_after (may be NULL) as in
+ * qjl_decode_attention_timed.
  */
 int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, const void* S_dual,
                               const uint8_t* bits, const uint16_t* norms_in,
                               const uint16_t* norms_out, const void* V, float* out, void* workspace,
-                              size_t workspace_bytes, void* stream);
+                              size_t workspace_bytes, void* stream, void* event_before,
+                              void* event_after);
 
 #ifdef __cplusplus
 }

@@ -75,7 +75,7 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_dual_workspace_bytes.restype = ctypes.c_size_t
     L.qjl_decode_dual_workspace_bytes.argtypes = [sp, ip]
     L.qjl_decode_attention_dual.restype = ctypes.c_int
-    L.qjl_decode_attention_dual.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_decode_attention_dual.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     _lib = L
     return L
 
@@ -279,8 +279,9 @@ def qjl_decode_dual_workspace_bytes(batch: int, q_heads: int, kv_heads: int, n: 
 def qjl_decode_attention_dual(Q: torch.Tensor, S_dual: torch.Tensor, bits: torch.Tensor,
                               norms_in: torch.Tensor, norms_out: torch.Tensor, V: torch.Tensor,
                               m_out: int, scale: float = 1.0, out: Optional[torch.Tensor] = None,
-                              workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """One decode step on a two-part cache: -> float32 [B,Hq,d]."""
+                              workspace: Optional[torch.Tensor] = None,
+                              events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
+    """One decode step on a two-part cache: -> float32 [B,Hq,d].  `events` as in qjl_decode_attention."""
     B, Hq, d = Q.shape
     _, Hkv, n, _ = V.shape
     mt = S_dual.shape[2]
@@ -302,5 +303,6 @@ def qjl_decode_attention_dual(Q: torch.Tensor, S_dual: torch.Tensor, bits: torch
                                            _dev(bits, "bits"), _dev(norms_in, "norms_in"),
                                            _dev(norms_out, "norms_out"), _dev(V, "V"), _dev(out, "out"),
                                            _dev(workspace, "workspace"),
-                                           workspace.numel() * workspace.element_size(), _stream(Q)))
+                                           workspace.numel() * workspace.element_size(), _stream(Q),
+                                           events[0] if events else None, events[1] if events else None))
     return out

@@ -158,7 +158,8 @@ size_t qjl_decode_dual_workspace_bytes(const qjl_shape* shape, int m_out) {
 int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, const void* S_dual,
                               const uint8_t* bits, const uint16_t* norms_in,
                               const uint16_t* norms_out, const void* V, float* out, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+                              size_t workspace_bytes, void* stream, void* event_before,
+                              void* event_after) {
   int rc = check_shape(shape);
   if (rc != QJL_OK) return rc;
   if (!ptr_ok(Q) || !ptr_ok(S_dual) || !ptr_ok(bits) || !ptr_ok(norms_in) || !ptr_ok(norms_out) ||
@@ -170,7 +171,8 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
   return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, out, workspace,
-                       static_cast<hipStream_t>(stream), nullptr, nullptr);
+                       static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
+                       static_cast<hipEvent_t>(event_after));
 }
 
 }  // extern "C"

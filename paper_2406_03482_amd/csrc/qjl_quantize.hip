@@ -80,7 +80,9 @@ template <> __device__ __forceinline__ float sumsq8<f16_t>(const uint4& u) {
 // outlier channels): the code is that of a stacked sketch whose rows already
 // exclude / keep only the head's `count` outlier channels, and two norms are
 // stored: of the key without those channels and of those channels alone.
-template <typename T, int PPW, bool DUAL>
+// CW = waves that run MFMAs (4, or 3 for code sizes that are 3 x 128 bits: the
+// fourth wave then only helps with loading and takes the norms).
+template <typename T, int PPW, bool DUAL, int CW>
 __global__ void __launch_bounds__(256, 2)
 quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S, size_t seg_stride,
                      uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
@@ -99,7 +101,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     }
   }
   constexpr int NA = PPW / 32;            // 32x32 MFMA tiles per wave along the projections
-  constexpr int WPT = 4 * PPW / 32;       // code words per key written by this workgroup
+  constexpr int WPT = CW * PPW / 32;      // code words per key written by this workgroup
   __shared__ uint4 kbuf[2][kTok * kRowU4];
   __shared__ uint4 obuf[2][kTok * WPT / 4];
   __shared__ float nsq[2][kTok];           // squared norms of the tile's keys
@@ -109,7 +111,8 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int h = lane >> 5;                // which 8 of the 16 k of an MFMA step this lane feeds
   const int j = lane & 31;                // A: row of the S tile, B/D: key of the sub-tile
-  const int proj_base = blockIdx.y * (4 * PPW) + wave * PPW;
+  const int proj_base = blockIdx.y * (CW * PPW) + wave * PPW;
+  const bool computes = CW == 4 || wave < CW;   // uniform per wave
   const int words_per_row = m >> 5;
 
   // ---- this wave's rows of S, resident in registers as MFMA A operands.
@@ -118,6 +121,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   // 8(v/4) + 4h + v%4) lane (h, j) then owns projections
   // proj_base + h*PPW/2 + 16a + v, v = 0..15 -- consecutive code bits of key j.
   frag sfrag[NA][8];
+  if (computes) {
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
     const int srow = proj_base + ((j >> 2) & 1) * (PPW / 2) + 16 * a + 4 * (j >> 3) + (j & 3);
@@ -127,6 +131,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
       uint4 u = sp[2 * s];
       __builtin_memcpy(&sfrag[a][s], &u, 16);
     }
+  }
   }
 
   // ---- loader: thread -> (row lrow + 16u, 16-byte column lcol) of a tile, u = 0..3
@@ -204,6 +209,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     // u-1 are extracted (v_alignbit) in the shadow of its MFMAs, and the B
     // operand of step g+2 is fetched from LDS, so the matrix pipe never waits
     // for the vector ALU or for LDS.  sched_barrier keeps that interleaving.
+    if (computes) {
     constexpr int NU = NA >= 2 ? NA : 1;
     auto sub_of = [](int u, int c) { return NA >= 2 ? u / (NA / 2) : c; };
     auto a_of = [](int u, int c) { return NA >= 2 ? 2 * (u % (NA / 2)) + c : 0; };
@@ -258,7 +264,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
       }
     }
     // lane (h, j) holds PPW/2 consecutive code bits of keys j and 32 + j, starting
-    // at bit wave*PPW + h*PPW/2 of this workgroup's 4*PPW
+    // at bit wave*PPW + h*PPW/2 of this workgroup's CW*PPW
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
       uint32_t* orow = reinterpret_cast<uint32_t*>(obuf[buf]) + (sub * 32 + j) * WPT;
@@ -270,6 +276,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
       } else {
         reinterpret_cast<uint16_t*>(orow)[wave * 2 + h] = (uint16_t)half[sub];
       }
+    }
     }
 
     if (has_next) stage_tile(buf ^ 1);
@@ -348,7 +355,7 @@ struct quant_io {
   int d, m;                                             // m = all code bits of a key
 };
 
-template <typename T, int PPW, bool DUAL>
+template <typename T, int PPW, bool DUAL, int CW>
 int launch_mfma(const quant_io& q, hipStream_t st) {
   const long tiles = (q.rows + kTok - 1) / kTok;
   if (tiles > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
@@ -357,8 +364,8 @@ int launch_mfma(const quant_io& q, hipStream_t st) {
   if (gx > tiles) gx = tiles;
   for (long s0 = 0; s0 < q.segments; s0 += 65535) {
     const long nz = q.segments - s0 < 65535 ? q.segments - s0 : 65535;
-    dim3 grid((unsigned)gx, (unsigned)(q.m / (4 * PPW)), (unsigned)nz);
-    hipLaunchKernelGGL((quantize_mfma_kernel<T, PPW, DUAL>), grid, dim3(256), 0, st,
+    dim3 grid((unsigned)gx, (unsigned)(q.m / (CW * PPW)), (unsigned)nz);
+    hipLaunchKernelGGL((quantize_mfma_kernel<T, PPW, DUAL, CW>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(q.K), static_cast<const uint16_t*>(q.S), q.seg_stride,
                        reinterpret_cast<uint32_t*>(q.bits), q.norms, q.norms_out, q.channels, q.count,
                        q.rows, q.m, (int)tiles, (int)s0);
@@ -368,9 +375,10 @@ int launch_mfma(const quant_io& q, hipStream_t st) {
 
 template <typename T, bool DUAL>
 int launch_mfma_m(const quant_io& q, hipStream_t st) {
-  if (q.m % 512 == 0) return launch_mfma<T, 128, DUAL>(q, st);
-  if (q.m % 256 == 0) return launch_mfma<T, 64, DUAL>(q, st);
-  return launch_mfma<T, 32, DUAL>(q, st);
+  if (q.m % 512 == 0) return launch_mfma<T, 128, DUAL, 4>(q, st);
+  if (q.m % 384 == 0) return launch_mfma<T, 128, DUAL, 3>(q, st);   // one pass over the keys instead of three
+  if (q.m % 256 == 0) return launch_mfma<T, 64, DUAL, 4>(q, st);
+  return launch_mfma<T, 32, DUAL, 4>(q, st);
 }
 
 template <typename T, bool DUAL>

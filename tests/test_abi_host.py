@@ -156,6 +156,6 @@ def test_dual_entry_points_validate_on_the_host(L):
     odd = QJLShape(1, 4, 2, 100, 128, 250, 2, 1.0)
     assert L.qjl_quantize_keys_dual(ctypes.byref(odd), 128, ok, ok, ok, 4, ok, ok, ok, None) == UNSUPPORTED
     assert L.qjl_decode_attention_dual(ctypes.byref(sh), 128, ok, ok, ok, ok, ok, ok, ok, vp(None),
-                                       ctypes.c_size_t(0), None) == WORKSPACE
+                                       ctypes.c_size_t(0), None, None, None) == WORKSPACE
     assert L.qjl_decode_attention_dual(ctypes.byref(sh), 64, ok, ok, ok, ok, ok, ok, ok, ok,
-                                       ctypes.c_size_t(1 << 30), None) == UNSUPPORTED
+                                       ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
