@@ -46,7 +46,6 @@ struct decode_args {
   float* out;             // [B,Hq,128]
   int n, groups_per_kv;
   int nsplit, chunk;
-  int bk0;                // first (batch, kv head) pair of this launch
   float coef2;            // scale * sqrt(pi/2) / m * log2(e); m = bits of the (first) code part
   float coef2b;           // the same for the second part
 };
@@ -156,11 +155,15 @@ decode_kernel(decode_args a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps block indices in SGPRs
-  // grid: x = chunk of the context, y = group of GT query heads, z = (batch, kv head).
+  // grid: x = (batch, kv head), y = group of GT query heads, z = chunk of the context.
   // Query heads of one kv head are consecutive, so the first head of this
   // workgroup is ((b * Hkv + kvh) * groups + group) * GT: no division needed.
-  const int split = blockIdx.x;
-  const int bk = a.bk0 + blockIdx.z;                  // b * Hkv + kvh
+  // With x fastest, workgroups are dealt to the eight XCDs by (batch, kv head):
+  // for head counts that are multiples of 8 all chunks and all query-head groups
+  // of a kv head run on one XCD and share its L2 (the head's sketch, and for
+  // grouped queries its codes and values).
+  const int split = blockIdx.z;
+  const int bk = blockIdx.x;                          // b * Hkv + kvh
   const size_t hq0 = ((size_t)bk * a.groups_per_kv + blockIdx.y) * GT;
 
   const int k_begin = split * a.chunk;
@@ -437,20 +440,14 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
   }
-  if (a.groups_per_kv > 65535) return QJL_ERR_UNSUPPORTED;
-  // grid z holds at most 65535 (batch, kv head) pairs: larger caches take several launches
   const long pairs = (long)sh.batch * sh.kv_heads;
-  for (long bk0 = 0; bk0 < pairs; bk0 += 65535) {
-    const long nz = pairs - bk0 < 65535 ? pairs - bk0 : 65535;
-    const dim3 grid((unsigned)plan.nsplit, (unsigned)a.groups_per_kv, (unsigned)nz);
-    a.bk0 = (int)bk0;
-    const bool first = bk0 == 0, last = bk0 + nz == pairs;
-    if ((ev0 && first) || (ev1 && last))   // the events take the kernels' own start and stop timestamps
-      hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
-                            first ? ev0 : nullptr, last ? ev1 : nullptr, 0u, a);
-    else
-      hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), lds, st, a);
-  }
+  if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
+  const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
+  if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+                          ev0, ev1, 0u, a);
+  else
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
@@ -553,7 +550,7 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);
   a.out = out;
-  a.n = sh.n; a.bk0 = 0;
+  a.n = sh.n;
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
