@@ -49,6 +49,19 @@ Readings of points the paper leaves open (all restated where they are used):
     query is split the same way and the two Eq. (4) estimates are added; a
     cache row is the inlier code followed by the outlier code.  These
     functions are pinned by tests/test_oracle_dual_pins.py.
+  * Value cache (Section 3.2): the paper says only "normalizing each token's
+    entries and then rounding each entry to a few-bit integer".  Read here as
+    the standard asymmetric token-wise scheme: per (batch, kv head, token)
+    zero point = the row's minimum, scale = (max - min)/(2^b - 1), both stored
+    in binary16; code = round-to-nearest-even of (v - min)/scale clipped to
+    [0, 2^b - 1], taken against the *stored* zero point and scale; b = 4 or 2;
+    element t of a row occupies bits [b*t, b*t + b) of the row's bytes, LSB
+    first; a value is read back as min + code * scale.  The code is an integer
+    decided by floating point, so it is computed in float32 with exactly the
+    operations written in `quantize_values` (the GPU uses the same ones);
+    everything after the code is float64.  Pinned by
+    tests/test_oracle_value_pins.py (round-trip bound, worked example,
+    invariances); the choice of scheme itself is this build's reading.
 
 Array conventions (all dense, C order):
     K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
@@ -331,3 +344,63 @@ def decode_attention_dual(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, V,
     """One decode step on a cache quantized by `quantize_keys_dual`."""
     return attention_from_scores(
         estimate_scores_dual(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, scale), V)
+
+
+# --------------------------------------------------------------------------
+# Section 3.2: token-wise quantization of the value cache
+# --------------------------------------------------------------------------
+def quantize_values(V: np.ndarray, vbits: int = 4):
+    """V [B,Hkv,n,d] (already exact in float32) -> (codes uint8 [B,Hkv,n,d*vbits/8],
+    scale float16 [B,Hkv,n], zero float16 [B,Hkv,n]).
+
+    Per row, in float32 (the precision in which the code is decided):
+        lo, hi   = min, max of the row
+        scale16  = binary16( (hi - lo) / (2^b - 1) )        zero16 = binary16(lo)
+        code_t   = clip( rint( (v_t - zero16) / scale16 ), 0, 2^b - 1 )   (0 if scale16 == 0)
+    """
+    if vbits not in (2, 4, 8):
+        raise ValueError("vbits must be 2, 4 or 8")
+    V32 = np.asarray(V, dtype=np.float32)
+    if not np.array_equal(V32.astype(np.float64), np.asarray(V, dtype=np.float64)):
+        raise ValueError("values must be exactly representable in float32")
+    levels = np.float32((1 << vbits) - 1)
+    lo = V32.min(axis=-1)
+    hi = V32.max(axis=-1)
+    scale16 = ((hi - lo) / levels).astype(np.float16)
+    zero16 = lo.astype(np.float16)
+    sc = scale16.astype(np.float32)[..., None]
+    z = zero16.astype(np.float32)[..., None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = np.rint((V32 - z) / sc)                       # float32 subtract, divide, round-half-even
+    q = np.where(sc > 0, np.clip(q, np.float32(0), levels), np.float32(0)).astype(np.uint8)
+    per = 8 // vbits                                      # elements per byte
+    d = q.shape[-1]
+    if d % per:
+        raise ValueError("d * vbits must be a multiple of 8")
+    grouped = q.reshape(q.shape[:-1] + (d // per, per)).astype(np.uint16)
+    packed = np.zeros(grouped.shape[:-1], dtype=np.uint16)
+    for t in range(per):
+        packed |= grouped[..., t] << (vbits * t)
+    return packed.astype(np.uint8), scale16, zero16
+
+
+def dequantize_values(codes: np.ndarray, scale16: np.ndarray, zero16: np.ndarray, vbits: int = 4) -> np.ndarray:
+    """Values as the cache represents them: zero + code * scale, float64 [B,Hkv,n,d]."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    per = 8 // vbits
+    mask = (1 << vbits) - 1
+    q = np.empty(codes.shape[:-1] + (codes.shape[-1] * per,), dtype=np.float64)
+    for t in range(per):
+        q[..., t::per] = ((codes >> (vbits * t)) & mask).astype(np.float64)
+    sc = np.asarray(scale16, dtype=np.float16).astype(np.float64)[..., None]
+    z = np.asarray(zero16, dtype=np.float16).astype(np.float64)[..., None]
+    return z + q * sc
+
+
+def decode_attention_vq(Q, S, bits, nu16, vcodes, vscale16, vzero16, vbits: int = 4,
+                        scale: float = 1.0) -> np.ndarray:
+    """One decode step with both caches quantized: Algorithm 1's scores from the
+    key code, softmax, and Eq. (1) on the values as stored (Section 3.2)."""
+    SQ = project_query(Q, S)
+    return attention_from_scores(estimate_scores(SQ, bits, nu16, scale),
+                                 dequantize_values(vcodes, vscale16, vzero16, vbits))
