@@ -72,7 +72,8 @@ class HipEvents:
 
 def decode_bytes_per_key(w) -> int:
     """Algorithmic HBM bytes per (batch, kv head, token): code + norm + one row of V."""
-    return (w.m + w.m_out) // 8 + (4 if w.m_out else 2) + w.d * 2
+    value_row = w.d * w.vbits // 8 + 4 if w.vbits else w.d * 2      # codes + scale + zero point, or 16-bit entries
+    return (w.m + w.m_out) // 8 + (4 if w.m_out else 2) + value_row
 
 
 def load_traffic(name: str):
@@ -104,14 +105,24 @@ def prepare_decode(qjl, inputs, w, dev):
         return dict(Q=Q, S=S, bits=bits, norms=norms, norms_out=norms_out, V=V, ws=ws, out=out)
     bits, norms = qjl.qjl_quantize_keys(K, S)       # untimed: the cache already exists at decode time
     del K
+    if w.vbits:                                     # value cache quantized token-wise (Section 3.2), also untimed
+        vc, vs, vz = qjl.qjl_quantize_values(V, w.vbits)
+        V = None
+        extra_v = dict(vcodes=vc, vscale=vs, vzero=vz)
+    else:
+        extra_v = {}
     ws = torch.empty((qjl.qjl_decode_workspace_bytes(w.batch, w.q_heads, w.kv_heads, w.n, w.d, w.m, w.dtype),),
                      dtype=torch.uint8, device=dev)
     out = torch.empty((w.batch, w.q_heads, w.d), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
-    return dict(Q=Q, S=S, bits=bits, norms=norms, V=V, ws=ws, out=out)
+    return dict(Q=Q, S=S, bits=bits, norms=norms, V=V, ws=ws, out=out, **extra_v)
 
 
 def run_decode(qjl, t, w, events=None):
+    if w.vbits:
+        qjl.qjl_decode_attention_vq(t["Q"], t["S"], t["bits"], t["norms"], t["vcodes"], t["vscale"], t["vzero"],
+                                    w.vbits, w.scale, out=t["out"], workspace=t["ws"], events=events)
+        return
     if w.m_out:
         qjl.qjl_decode_attention_dual(t["Q"], t["S"], t["bits"], t["norms"], t["norms_out"], t["V"], w.m_out,
                                       w.scale, out=t["out"], workspace=t["ws"], events=events)
@@ -228,6 +239,40 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     }
 
 
+def bench_value_quantize(qjl, inputs, ev, w, dev, steps, warmup):
+    """Token-wise 4-bit quantization of a value cache of the prefill workload's shape (HBM-bound)."""
+    import torch
+    V = inputs.make_normal((w.batch, w.kv_heads, w.n, w.d), w.dtype, w.data_seed + 104729, dev)
+    vc = torch.empty((w.batch, w.kv_heads, w.n, w.d // 2), dtype=torch.uint8, device=dev)
+    vs = torch.empty((w.batch, w.kv_heads, w.n), dtype=torch.float16, device=dev)
+    vz = torch.empty_like(vs)
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(warmup):
+        qjl.qjl_quantize_values(V, 4, vc, vs, vz)
+    torch.cuda.synchronize()
+    a, b = ev.create(), ev.create()
+    ev.record(a, stream)
+    for _ in range(steps):
+        qjl.qjl_quantize_values(V, 4, vc, vs, vz)
+    ev.record(b, stream)
+    ms = ev.elapsed_ms(a, b) / steps
+    ev.destroy(a)
+    ev.destroy(b)
+    rows = w.batch * w.kv_heads * w.n
+    algo_bytes = rows * (w.d * 2 + w.d // 2 + 4)
+    achieved = algo_bytes / (ms * 1e-3) / 1e9
+    return {
+        "workload": w.name + "_values_v4",
+        "metric": "prefill value quantize tokens/s",
+        "value": w.batch * w.n / (ms * 1e-3),
+        "rows_per_s": rows / (ms * 1e-3),
+        "ms_per_step": ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "value_quant4_kernel",
+                     "kernel_ms": ms, "algorithmic_bytes": algo_bytes},
+    }
+
+
 def cpu_baseline(inputs, w, budget_s=12.0):
     """The oracle, as it stands, on the host cores: the same decode step
     (project -> scores -> softmax -> values) on the same workload."""
@@ -261,7 +306,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
                     "metric is quoted on), c3, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
-                    "quantized separately), for profiling single kernels; "
+                    "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache), for profiling single kernels; "
                     "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -323,7 +368,7 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
-                   "context": w.n, "d": w.d, "m": w.m, "m_out": w.m_out, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
+                   "context": w.n, "d": w.d, "m": w.m, "m_out": w.m_out, "vbits": w.vbits, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
         "roofline": head["roofline"],
     }
 
@@ -331,7 +376,8 @@ def main() -> int:
         extra = []
         for name, steps, warm in [("c3_long_context_b4_32k", 100, 20), ("c5a_llama3_8b_gqa_b1_128k", 200, 20),
                                   ("c5b_llama3_8b_gqa_b16_8k", 200, 20), ("c2d_llama2_7b_decode_4k_dual", 400, 40),
-                                  ("c3d_long_context_b4_32k_dual", 100, 20)]:
+                                  ("c3d_long_context_b4_32k_dual", 100, 20), ("c2v_llama2_7b_decode_4k_v4", 400, 40),
+                                  ("c3v_long_context_b4_32k_v4", 100, 20), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20)]:
             wx = inputs.WORKLOADS[name]
             tx = prepare_decode(qjl, inputs, wx, dev)
             extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm)))
@@ -339,9 +385,10 @@ def main() -> int:
             torch.cuda.empty_cache()
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 50, 5))
+        extra.append(bench_value_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         line["other_workloads"] = extra
 
-    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out:
+    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out and not w.vbits:
         line["cpu_baseline"] = cpu_baseline(inputs, w)
     else:
         line["cpu_baseline"] = None

@@ -216,6 +216,35 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
                               size_t workspace_bytes, void* stream, void* event_before,
                               void* event_after);
 
+/* ------------------------------------------------------------------------
+ * Value cache (Section 3.2): "normalizing each token's entries and then
+ * rounding each entry to a few-bit integer".  Scheme used: per (batch, kv
+ * head, token) zero point = the row's minimum, scale = (max - min)/(2^b - 1),
+ * both stored as binary16; code = (v - zero)/scale rounded to nearest (ties to
+ * even), clipped to [0, 2^b - 1], taken in float32 against the stored zero
+ * point and scale; element t of a row occupies bits [b*t, b*t + b) of the
+ * row's d*b/8 bytes (LSB first); a value reads back as zero + code * scale.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * vcodes[B,Hkv,n,d*vbits/8], vscale[B,Hkv,n], vzero[B,Hkv,n] (binary16) <-
+ * V[B,Hkv,n,d] of type shape->dtype.  Supported: vbits == 4, d == 128.
+ */
+int qjl_quantize_values(const qjl_shape* shape, int vbits, const void* V, uint8_t* vcodes,
+                        uint16_t* vscale, uint16_t* vzero, void* stream);
+
+/*
+ * qjl_decode_attention with the values taken from a cache written by
+ * qjl_quantize_values: out[B,Hq,d] <- sum_j softmax_j(...) * (vzero[j] + vscale[j] * code[j,:]).
+ * Supported: vbits == 4, d == 128, 16-bit shape->dtype (type of Q and S).
+ * Workspace: qjl_decode_workspace_bytes(shape); events as in qjl_decode_attention_timed.
+ */
+int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, const void* S,
+                            const uint8_t* bits, const uint16_t* norms, const uint8_t* vcodes,
+                            const uint16_t* vscale, const uint16_t* vzero, float* out,
+                            void* workspace, size_t workspace_bytes, void* stream,
+                            void* event_before, void* event_after);
+
 #ifdef __cplusplus
 }
 #endif

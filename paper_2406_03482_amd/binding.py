@@ -76,6 +76,10 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_dual_workspace_bytes.argtypes = [sp, ip]
     L.qjl_decode_attention_dual.restype = ctypes.c_int
     L.qjl_decode_attention_dual.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    L.qjl_quantize_values.restype = ctypes.c_int
+    L.qjl_quantize_values.argtypes = [sp, ip, vp, vp, vp, vp, vp]
+    L.qjl_decode_attention_vq.restype = ctypes.c_int
+    L.qjl_decode_attention_vq.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     _lib = L
     return L
 
@@ -305,4 +309,54 @@ def qjl_decode_attention_dual(Q: torch.Tensor, S_dual: torch.Tensor, bits: torch
                                            _dev(workspace, "workspace"),
                                            workspace.numel() * workspace.element_size(), _stream(Q),
                                            events[0] if events else None, events[1] if events else None))
+    return out
+
+
+# ---- value cache quantization (Section 3.2)
+def qjl_quantize_values(V: torch.Tensor, vbits: int = 4, vcodes: Optional[torch.Tensor] = None,
+                        vscale: Optional[torch.Tensor] = None, vzero: Optional[torch.Tensor] = None):
+    """V[B,Hkv,n,d] -> (codes uint8 [B,Hkv,n,d*vbits/8], scale float16 [B,Hkv,n], zero float16 [B,Hkv,n])."""
+    B, Hkv, n, d = V.shape
+    if vcodes is None:
+        vcodes = torch.empty((B, Hkv, n, d * vbits // 8), dtype=torch.uint8, device=V.device)
+    if vscale is None:
+        vscale = torch.empty((B, Hkv, n), dtype=torch.float16, device=V.device)
+    if vzero is None:
+        vzero = torch.empty((B, Hkv, n), dtype=torch.float16, device=V.device)
+    if tuple(vcodes.shape) != (B, Hkv, n, d * vbits // 8) or vcodes.dtype != torch.uint8:
+        raise ValueError("vcodes must be uint8 [B,Hkv,n,d*vbits/8]")
+    sh = _shape(B, Hkv, Hkv, n, d, 32, _tag(V))
+    _check("qjl_quantize_values",
+           lib().qjl_quantize_values(ctypes.byref(sh), vbits, _dev(V, "V"), _dev(vcodes, "vcodes"),
+                                     _dev(vscale, "vscale"), _dev(vzero, "vzero"), _stream(V)))
+    return vcodes, vscale, vzero
+
+
+def qjl_decode_attention_vq(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor,
+                            vcodes: torch.Tensor, vscale: torch.Tensor, vzero: torch.Tensor, vbits: int = 4,
+                            scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None,
+                            events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
+    """One decode step with quantized keys and values -> float32 [B,Hq,d]."""
+    B, Hq, d = Q.shape
+    _, Hkv, n, vb = vcodes.shape
+    m = S.shape[0]
+    if S.dtype != Q.dtype or vb * 8 != d * vbits:
+        raise ValueError("S must have the dtype of Q; vcodes must be [B,Hkv,n,d*vbits/8]")
+    if tuple(bits.shape) != (B, Hkv, n, m // 8) or tuple(norms.shape) != (B, Hkv, n):
+        raise ValueError("bits/norms do not match the value cache and S")
+    if tuple(vscale.shape) != (B, Hkv, n) or tuple(vzero.shape) != (B, Hkv, n):
+        raise ValueError("vscale/vzero must be [B,Hkv,n]")
+    need = qjl_decode_workspace_bytes(B, Hq, Hkv, n, d, m, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, n, d, m, _tag(Q), scale)
+    _check("qjl_decode_attention_vq",
+           lib().qjl_decode_attention_vq(ctypes.byref(sh), vbits, _dev(Q, "Q"), _dev(S, "S"), _dev(bits, "bits"),
+                                         _dev(norms, "norms"), _dev(vcodes, "vcodes"), _dev(vscale, "vscale"),
+                                         _dev(vzero, "vzero"), _dev(out, "out"), _dev(workspace, "workspace"),
+                                         workspace.numel() * workspace.element_size(), _stream(Q),
+                                         events[0] if events else None, events[1] if events else None))
     return out

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqjl.so")
 SOURCES = ["qjl_api.hip", "qjl_sketch.hip", "qjl_project.hip", "qjl_quantize.hip",
-           "qjl_scores.hip", "qjl_decode.hip", "qjl_outlier.hip"]
+           "qjl_scores.hip", "qjl_decode.hip", "qjl_outlier.hip", "qjl_values.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -100,7 +100,7 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
   if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
 }
@@ -170,7 +170,38 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
   if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, out, workspace,
+  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, nullptr, nullptr, out,
+                       workspace,
+                       static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
+                       static_cast<hipEvent_t>(event_after));
+}
+
+int qjl_quantize_values(const qjl_shape* shape, int vbits, const void* V, uint8_t* vcodes,
+                        uint16_t* vscale, uint16_t* vzero, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(V) || !ptr_ok(vcodes) || !ptr_ok(vscale) || !ptr_ok(vzero)) return QJL_ERR_INVALID_ARG;
+  if (vbits < 1 || vbits > 8) return QJL_ERR_INVALID_ARG;
+  return launch_quantize_values(*shape, vbits, V, vcodes, vscale, vzero, static_cast<hipStream_t>(stream));
+}
+
+int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, const void* S,
+                            const uint8_t* bits, const uint16_t* norms, const uint8_t* vcodes,
+                            const uint16_t* vscale, const uint16_t* vzero, float* out, void* workspace,
+                            size_t workspace_bytes, void* stream, void* event_before,
+                            void* event_after) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(vcodes) || !ptr_ok(vscale) ||
+      !ptr_ok(vzero) || !ptr_ok(out))
+    return QJL_ERR_INVALID_ARG;
+  if (vbits < 1 || vbits > 8) return QJL_ERR_INVALID_ARG;
+  if (vbits != 4 || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
+  decode_plan plan;
+  if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, vcodes, vscale, vzero, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
 }

@@ -96,6 +96,13 @@ __device__ __forceinline__ float row16_max(float v) {
   v = fmaxf(v, QJL_DPP_F(v, 0x140));
   return v;
 }
+__device__ __forceinline__ float row16_min(float v) {
+  v = fminf(v, QJL_DPP_F(v, 0xB1));
+  v = fminf(v, QJL_DPP_F(v, 0x4E));
+  v = fminf(v, QJL_DPP_F(v, 0x141));
+  v = fminf(v, QJL_DPP_F(v, 0x140));
+  return v;
+}
 __device__ __forceinline__ float wave_sum(float v) {
   v = row16_sum(v);
   float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
@@ -136,6 +143,8 @@ int launch_select_outliers(const qjl_shape& sh, const void* K, int count, int32_
                            void* workspace, hipStream_t st);
 int launch_make_dual_sketch(const qjl_shape& sh, int m_out, const void* S_in, const void* S_out,
                             const int32_t* channels, int count, void* S_dual, hipStream_t st);
+int launch_quantize_values(const qjl_shape& sh, int vbits, const void* V, uint8_t* codes,
+                           uint16_t* vscale, uint16_t* vzero, hipStream_t st);
 int launch_project(int rows, int d, int m, int dtype, const void* Q, const void* S, float* SQ,
                    hipStream_t st);
 int launch_scores(const qjl_shape& sh, const float* SQ, const uint8_t* bits,
@@ -150,11 +159,13 @@ struct decode_plan {
 };
 // m_out = 0: one code per key (sh.m bits, one shared sketch S[m,d]).  m_out > 0: a key's
 // code is sh.m + m_out bits of two independent instances with a norm each, and S
-// holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).
+// holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).  vscale != nullptr: V holds
+// 4-bit value codes with a binary16 scale and zero point per token.
 bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  float* out, void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
+                  const uint16_t* vscale, const uint16_t* vzero, float* out, void* workspace,
+                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
 int device_cu_count();
 
 }  // namespace qjl

@@ -14,6 +14,7 @@
 #include "qjl_lut.hpp"
 
 #include <hip/hip_ext.h>
+#include <type_traits>
 #include <stdlib.h>
 
 namespace qjl {
@@ -41,7 +42,9 @@ struct decode_args {
   const uint16_t* norms;  // [B,Hkv,n]
   const uint16_t* norms2; // [B,Hkv,n] norm of the outlier part (two-part codes only)
   size_t s_head_stride;   // elements between the sketches of consecutive (batch, kv head) pairs
-  const void* V;          // [B,Hkv,n,128]
+  const void* V;          // [B,Hkv,n,128], or the 4-bit codes [B,Hkv,n,64 bytes] of quantized values
+  const uint16_t* vscale; // [B,Hkv,n] binary16 scale and zero point of a token's values (quantized values only)
+  const uint16_t* vzero;
   float* part;            // [B,Hq,nsplit,132]
   float* out;             // [B,Hq,128]
   int n, groups_per_kv;
@@ -132,7 +135,34 @@ __device__ __forceinline__ float dot8(const slice8<f32_t>& s, const slice8<f32_t
 // channels) with its own norm; a.S then points to per-head sketches whose rows
 // are already restricted to the coordinates of each instance, so S q needs no
 // special case, and the two partial inner products are weighted separately.
-template <typename T, int GT, int MW, int MWB>
+// ... or 4 bytes: eight 4-bit codes of a quantized value row (Section 3.2).  The
+// codes come out as floats 0..15; scale and zero point are applied per row.
+struct vtile_q4 {
+  uint32_t r;
+  __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
+    r = *reinterpret_cast<const uint32_t*>(static_cast<const char*>(V) + byte_off);
+  }
+  // One code per byte, then one v_cvt_f32_ubyteN per code (11 instructions per
+  // row instead of 16).  The conversions are written as asm because the
+  // compiler otherwise extracts every code with its own bit-field instruction.
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    const uint32_t even = r & 0x0F0F0F0Fu, odd = (r >> 4) & 0x0F0F0F0Fu;
+    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(even));
+    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[1]) : "v"(odd));
+    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[2]) : "v"(even));
+    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[3]) : "v"(odd));
+    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[4]) : "v"(even));
+    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[5]) : "v"(odd));
+    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[6]) : "v"(even));
+    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[7]) : "v"(odd));
+  }
+};
+
+// VQ: the values are stored as 4-bit codes with a binary16 scale and zero point
+// per token (Section 3.2).  o = sum_j p_j (zero_j + scale_j c_j): the weight
+// that goes to the value pass is p_j scale_j, and sum_j p_j zero_j, the same for
+// every channel, is carried next to the softmax denominator.
+template <typename T, int GT, int MW, int MWB, bool VQ>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
                                   T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
@@ -196,10 +226,12 @@ decode_kernel(decode_args a) {
   uint16_t ncur = 0;   // norm of this lane's key, still as binary16: converting it where it is
                        // loaded would make the wave wait for the load (and every older one) there
   uint16_t ncur2 = 0;  // norm of the second code part
+  uint16_t vscur = 0, vzcur = 0;   // scale and zero point of this lane's key's values
   // V rows in flight per lane: 16 (a whole 64-key block ahead), or 8 where the
   // four-head group needs the registers for its accumulators and tables
   constexpr int VD = GT == 4 ? 8 : 16;
-  vtile<T> v[VD];
+  using VT = typename std::conditional<VQ, vtile_q4, vtile<T>>::type;
+  VT v[VD];
   // V loads requested before the tables are built: enough to keep HBM busy
   // meanwhile, few enough that the rows of S (requested just before them, and
   // on the critical path) are not held up behind them
@@ -207,9 +239,14 @@ decode_kernel(decode_args a) {
   // row (4i + r) of the block starting at key kb: uniform base pointer + a
   // 32-bit lane offset, the row clamped to the last key of the chunk
   auto issue_v = [&](int slot, int i, int kb, int last_row) {   // row pass i of block kb -> v[slot]
-    const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * T::bytes);
     const int rr = min(4 * i + r, last_row);
-    v[slot].load(base, (uint32_t)(rr * kD + c * 8));
+    if constexpr (VQ) {
+      const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD / 2);
+      v[slot].load(base, (uint32_t)(rr * (kD / 2) + c * 4));
+    } else {
+      const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * T::bytes);
+      v[slot].load(base, (uint32_t)(rr * kD + c * 8));
+    }
   };
   // No branch around these loads (a wave whose first block lies past the chunk
   // end reads the chunk's last key instead and never uses it): with straight-line
@@ -220,6 +257,7 @@ decode_kernel(decode_args a) {
     load_code<MW>(a.bits, row0 + j, wcur);
     ncur = a.norms[row0 + j];
     if constexpr (MWB > 0) ncur2 = a.norms2[row0 + j];
+    if constexpr (VQ) { vscur = a.vscale[row0 + j]; vzcur = a.vzero[row0 + j]; }
 #pragma unroll
     for (int i = 0; i < VP; ++i) {
       issue_v(i, i, kf, k_end - 1 - kf);
@@ -253,10 +291,10 @@ decode_kernel(decode_args a) {
   // lut_build ends with a barrier: nobody reads `nib` any more.
 
   using PV = typename vecf<GT>::type;
-  float m_run[GT], l_lane[GT];
+  float m_run[GT], l_lane[GT], z_lane[GT];            // z: sum of p * zero point (quantized values)
   PV acc[8];                                          // acc[e] holds channel 8c+e of all GT heads
 #pragma unroll
-  for (int g = 0; g < GT; ++g) { m_run[g] = -INFINITY; l_lane[g] = 0.f; }
+  for (int g = 0; g < GT; ++g) { m_run[g] = -INFINITY; l_lane[g] = 0.f; z_lane[g] = 0.f; }
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
@@ -270,6 +308,8 @@ decode_kernel(decode_args a) {
     const bool valid = (k0 + lane) < k_end;
     const float nu = f16_bits_to_float(ncur) * a.coef2;
     const float nu2 = MWB > 0 ? f16_bits_to_float(ncur2) * a.coef2b : 0.f;
+    const float vs = VQ ? f16_bits_to_float(vscur) : 1.f;
+    const float vz = VQ ? f16_bits_to_float(vzcur) : 0.f;
     // the code registers are free again: fetch the next block's codes and norm
     // into them now, the value pass below hides the latency
     if (have_next) {
@@ -277,6 +317,7 @@ decode_kernel(decode_args a) {
       load_code<MW>(a.bits, row0 + j, wcur);
       ncur = a.norms[row0 + j];
       if constexpr (MWB > 0) ncur2 = a.norms2[row0 + j];
+      if constexpr (VQ) { vscur = a.vscale[row0 + j]; vzcur = a.vzero[row0 + j]; }
     }
     PV alpha, p;
 #pragma unroll
@@ -288,8 +329,9 @@ decode_kernel(decode_args a) {
       const float al = __builtin_amdgcn_exp2f(m_run[g] - m_new);
       const float pg = __builtin_amdgcn_exp2f(sg - m_new);
       vset<GT>(alpha, g, al);
-      vset<GT>(p, g, pg);
+      vset<GT>(p, g, VQ ? pg * vs : pg);
       l_lane[g] = l_lane[g] * al + pg;
+      if constexpr (VQ) z_lane[g] = z_lane[g] * al + pg * vz;
       m_run[g] = m_new;
     }
     // key (4i + r) of the block goes to slot r*16 + i, so that a V lane reads
@@ -338,6 +380,7 @@ decode_kernel(decode_args a) {
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     const float l = wave_sum(l_lane[g]);
+    const float zsum = VQ ? wave_sum(z_lane[g]) : 0.f;
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -351,7 +394,7 @@ decode_kernel(decode_args a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = o[e];
     }
-    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l; }
+    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l; rec[2] = zsum; }
   }
   __syncthreads();
 
@@ -361,20 +404,21 @@ decode_kernel(decode_args a) {
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) mx = fmaxf(mx, merge[(w * GT + g) * kPartStride]);
-    float L = 0.f, O = 0.f;
+    float L = 0.f, O = 0.f, Z = 0.f;
 #pragma unroll
     for (int w = 0; w < kNW; ++w) {
       const float* rec = merge + (w * GT + g) * kPartStride;
       const float f = __builtin_amdgcn_exp2f(rec[0] - mx);
       L = fmaf(rec[1], f, L);
+      if constexpr (VQ) Z = fmaf(rec[2], f, Z);
       O = fmaf(rec[4 + ch], f, O);
     }
     if (a.nsplit == 1) {
-      a.out[(hq0 + g) * kD + ch] = O / L;
+      a.out[(hq0 + g) * kD + ch] = (O + Z) / L;
     } else {
       float* rec = a.part + ((hq0 + g) * a.nsplit + split) * kPartStride;
       rec[4 + ch] = O;
-      if (ch == 0) { rec[0] = mx; rec[1] = L; }
+      if (ch == 0) { rec[0] = mx; rec[1] = L; rec[2] = Z; }
     }
   }
 }
@@ -387,14 +431,14 @@ decode_kernel(decode_args a) {
 // with up to 16 chunks costs a single round trip to memory.
 __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict__ part,
                                                          float* __restrict__ out, int nsplit) {
-  __shared__ float s_m[512], s_l[512];   // per chunk: running max and sum (nsplit <= 512)
-  __shared__ float s_o[kD], s_lsum;
+  __shared__ float s_m[512], s_l[512], s_z[512];   // per chunk: running max, sum, zero-point sum (nsplit <= 512)
+  __shared__ float s_o[kD], s_lsum, s_zsum;
   const size_t head = blockIdx.x;
   const int tid = threadIdx.x;
   const float* base = part + head * (size_t)nsplit * kPartStride;
   const int ch = tid & (kD - 1), half = tid >> 7;
   constexpr int kB = 8;                  // chunks per thread and pass
-  float O = 0.f, L = 0.f, mx = -INFINITY;
+  float O = 0.f, L = 0.f, Zc = 0.f, mx = -INFINITY;
   for (int s0 = 0; s0 < nsplit; s0 += 2 * kB) {
     float o[kB];
 #pragma unroll
@@ -406,6 +450,7 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
       for (int s2 = tid; s2 < nsplit; s2 += 2 * kD) {
         s_m[s2] = base[(size_t)s2 * kPartStride];
         s_l[s2] = base[(size_t)s2 * kPartStride + 1];
+        s_z[s2] = base[(size_t)s2 * kPartStride + 2];   // 0 unless the values are quantized
       }
       __syncthreads();
       for (int s2 = 0; s2 < nsplit; ++s2) mx = fmaxf(mx, s_m[s2]);
@@ -417,25 +462,26 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
         const float f = __builtin_amdgcn_exp2f(s_m[s2] - mx);
         O = fmaf(o[u], f, O);
         L = fmaf(s_l[s2], f, L);
+        Zc = fmaf(s_z[s2], f, Zc);
       }
     }
   }
   if (half == 1) {
     s_o[ch] = O;
-    if (ch == 0) s_lsum = L;
+    if (ch == 0) { s_lsum = L; s_zsum = Zc; }
   }
   __syncthreads();
-  if (half == 0) out[head * kD + ch] = (O + s_o[ch]) / (L + s_lsum);
+  if (half == 0) out[head * kD + ch] = (O + s_o[ch] + Zc + s_zsum) / (L + s_lsum);
 }
 
-template <typename T, int GT, int MW, int MWB>
+template <typename T, int GT, int MW, int MWB, bool VQ>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   static bool attr_set = false;
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   const size_t lds = decode_lds_bytes(GT, MW * 32);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VQ>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
@@ -444,20 +490,20 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
   if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
   if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
-    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VQ>), grid, dim3(kNW * 64), (uint32_t)lds, st,
                           ev0, ev1, 0u, a);
   else
-    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB>), grid, dim3(kNW * 64), lds, st, a);
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VQ>), grid, dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
-template <typename T, int MW, int MWB>
+template <typename T, int MW, int MWB, bool VQ = false>
 int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   switch (plan.gt) {
-    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    default: return launch_t<T, 1, MW, MWB>(sh, plan, a, st, ev0, ev1);
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1);
   }
 }
 
@@ -465,6 +511,19 @@ int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a,
 template <typename T>
 int launch_m(const qjl_shape& sh, int m_out, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
+  if (a.vscale != nullptr) {                        // quantized values: 16-bit queries, one-part codes
+    if constexpr (T::bytes == 2) {
+      if (m_out != 0) return QJL_ERR_UNSUPPORTED;
+      switch (sh.m) {
+        case 128: return launch_g<T, 4, 0, true>(sh, plan, a, st, ev0, ev1);
+        case 256: return launch_g<T, 8, 0, true>(sh, plan, a, st, ev0, ev1);
+        case 512: return launch_g<T, 16, 0, true>(sh, plan, a, st, ev0, ev1);
+        default: return QJL_ERR_UNSUPPORTED;
+      }
+    } else {
+      return QJL_ERR_UNSUPPORTED;
+    }
+  }
   if (m_out == 0) {
     switch (sh.m) {
       case 128: return launch_g<T, 4, 0>(sh, plan, a, st, ev0, ev1);
@@ -540,12 +599,14 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
 
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  float* out, void* workspace, hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
+                  const uint16_t* vscale, const uint16_t* vzero, float* out, void* workspace,
+                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
   decode_args a;
   a.Q = Q; a.S = S; a.bits = bits; a.norms = norms; a.V = V;
   a.norms2 = norms_out;
+  a.vscale = vscale; a.vzero = vzero;
   a.s_head_stride = m_out > 0 ? (size_t)(sh.m + m_out) * kD : 0;
   a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);

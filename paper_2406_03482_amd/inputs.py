@@ -35,6 +35,7 @@ class Workload:
     sketch_seed: int
     outliers: int = 4
     m_out: int = 0          # > 0: outlier channels get a second sketch of m_out rows (m is the inlier sketch)
+    vbits: int = 0          # > 0: the value cache is quantized token-wise to vbits bits per entry
 
     @property
     def key_heads(self) -> int:
@@ -60,6 +61,10 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("c2d_llama2_7b_decode_4k_dual", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, m_out=128),
     Workload("c3d_long_context_b4_32k_dual", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, m_out=128),
     Workload("c4d_prefill_quantize_64k_dual", 1, 32, 32, 65536, 128, 256, torch.bfloat16, _RS, 1004, 4, m_out=128),
+    # the decode shapes with a 4-bit value cache as well (Section 3.2)
+    Workload("c2v_llama2_7b_decode_4k_v4", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, vbits=4),
+    Workload("c3v_long_context_b4_32k_v4", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=4),
+    Workload("c5bv_llama3_8b_gqa_b16_8k_v4", 16, 32, 8, 8192, 128, 256, torch.bfloat16, _RS, 1006, 5, vbits=4),
 ]}
 
 

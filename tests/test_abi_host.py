@@ -31,10 +31,10 @@ def _declared_symbols():
 def test_header_symbols_are_exported(L):
     names = _declared_symbols()
     assert names == ["qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
-                     "qjl_decode_dual_workspace_bytes", "qjl_decode_workspace_bytes",
+                     "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_workspace_bytes",
                      "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_outlier_workspace_bytes",
-                     "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_scores",
-                     "qjl_select_outliers", "qjl_status_string", "qjl_version"]
+                     "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_quantize_values",
+                     "qjl_scores", "qjl_select_outliers", "qjl_status_string", "qjl_version"]
     for n in names:
         assert hasattr(L, n), n
 
@@ -159,3 +159,21 @@ def test_dual_entry_points_validate_on_the_host(L):
                                        ctypes.c_size_t(0), None, None, None) == WORKSPACE
     assert L.qjl_decode_attention_dual(ctypes.byref(sh), 64, ok, ok, ok, ok, ok, ok, ok, ok,
                                        ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
+
+
+def test_value_cache_entry_points_validate_on_the_host(L):
+    sh = QJLShape(1, 4, 2, 100, 128, 256, 2, 1.0)
+    ok = ctypes.c_void_p(0x1000)
+    vp = ctypes.c_void_p
+    assert L.qjl_quantize_values(ctypes.byref(sh), 4, vp(None), ok, ok, ok, None) == INVALID
+    assert L.qjl_quantize_values(ctypes.byref(sh), 0, ok, ok, ok, ok, None) == INVALID
+    assert L.qjl_quantize_values(ctypes.byref(sh), 2, ok, ok, ok, ok, None) == UNSUPPORTED      # only 4-bit codes are built
+    d64 = QJLShape(1, 4, 2, 100, 64, 256, 2, 1.0)
+    assert L.qjl_quantize_values(ctypes.byref(d64), 4, ok, ok, ok, ok, None) == UNSUPPORTED
+    args = (ok, ok, ok, ok, ok, ok, ok, ok)
+    assert L.qjl_decode_attention_vq(ctypes.byref(sh), 4, *args, vp(None), ctypes.c_size_t(0), None, None, None) == WORKSPACE
+    assert L.qjl_decode_attention_vq(ctypes.byref(sh), 2, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
+    f32 = QJLShape(1, 4, 2, 100, 128, 256, 0, 1.0)
+    assert L.qjl_decode_attention_vq(ctypes.byref(f32), 4, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
+    assert L.qjl_decode_attention_vq(ctypes.byref(sh), 4, ok, ok, ok, ok, vp(None), ok, ok, ok, ok,
+                                     ctypes.c_size_t(1 << 30), None, None, None) == INVALID
