@@ -62,6 +62,17 @@ Readings of points the paper leaves open (all restated where they are used):
     everything after the code is float64.  Pinned by
     tests/test_oracle_value_pins.py (round-trip bound, worked example,
     invariances); the choice of scheme itself is this build's reading.
+  * Orthogonalised sketch (Section 4.1, "Orthogonalized JL transform"): the
+    paper draws S i.i.d. Gaussian and orthogonalises its rows by QR; with
+    m > d not all rows can be orthogonal, and the paper does not say what a
+    row's length becomes.  Read here as: rows are taken in blocks of d; inside
+    a block row i is replaced by the i-th Gram-Schmidt direction of the
+    block's rows (the Q factor of the QR decomposition of the block's
+    transpose, signs fixed so that R has a positive diagonal), scaled back to
+    the length the Gaussian row had.  Row lengths and directions of a Gaussian
+    matrix are independent, so every row is still N(0, I) on its own and
+    Lemma 3.2 holds unchanged; only rows of the same block are now orthogonal.
+    Pinned by tests/test_oracle_orth_pins.py.
 
 Array conventions (all dense, C order):
     K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
@@ -404,3 +415,21 @@ def decode_attention_vq(Q, S, bits, nu16, vcodes, vscale16, vzero16, vbits: int 
     SQ = project_query(Q, S)
     return attention_from_scores(estimate_scores(SQ, bits, nu16, scale),
                                  dequantize_values(vcodes, vscale16, vzero16, vbits))
+
+
+# --------------------------------------------------------------------------
+# Section 4.1: orthogonalised rows
+# --------------------------------------------------------------------------
+def orthogonal_sketch(seed: int, m: int, d: int, dtype: str = "f32") -> np.ndarray:
+    """The Gaussian sketch of `gaussian_sketch(seed, m, d, "f32")` with the rows of
+    every block of d rows orthogonalised (QR) and rescaled to their original
+    lengths; float64 arithmetic, then rounded to the storage type ("f64": not
+    rounded at all)."""
+    G = gaussian_sketch(seed, m, d, "f32")
+    S = np.empty_like(G)
+    for r0 in range(0, m, d):
+        Gb = G[r0:r0 + d]                                   # [r, d], r <= d
+        Qt, R = np.linalg.qr(Gb.T)                          # Gb^T = Qt R ; columns of Qt: orthonormalised rows of Gb, in order
+        Qt = Qt * np.sign(np.diag(R))[None, :]              # Gram-Schmidt's choice of sign: R_ii > 0
+        S[r0:r0 + d] = np.linalg.norm(Gb, axis=1)[:, None] * Qt.T
+    return S if dtype == "f64" else round_to_storage(S, dtype)
