@@ -273,6 +273,26 @@ def bench_value_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     }
 
 
+def bench_sketches(qjl, ev, dev):
+    """One-off set-up kernels: the Gaussian sketch and its orthogonalised variant (Section 4.1), 256 x 128 bf16."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"workload": "sketch_256x128_bf16", "metric": "set-up kernel time", "unit": "us"}
+    for name, fn in (("make_sketch_us", qjl.qjl_make_sketch), ("make_sketch_orthogonal_us", qjl.qjl_make_sketch_orthogonal)):
+        for _ in range(3):
+            fn(1, 256, 128, torch.bfloat16, dev)
+        torch.cuda.synchronize()
+        a, b = ev.create(), ev.create()
+        ev.record(a, stream)
+        for _ in range(20):
+            fn(1, 256, 128, torch.bfloat16, dev)
+        ev.record(b, stream)
+        out[name] = ev.elapsed_ms(a, b) / 20 * 1e3
+        ev.destroy(a)
+        ev.destroy(b)
+    return out
+
+
 def cpu_baseline(inputs, w, budget_s=12.0):
     """The oracle, as it stands, on the host cores: the same decode step
     (project -> scores -> softmax -> values) on the same workload."""
@@ -386,6 +406,7 @@ def main() -> int:
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 50, 5))
         extra.append(bench_value_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
+        line["setup_kernels"] = bench_sketches(qjl, ev, dev)
         line["other_workloads"] = extra
 
     if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out and not w.vbits:

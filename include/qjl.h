@@ -76,6 +76,18 @@ const char* qjl_status_string(int status);
 int qjl_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, void* stream);
 
 /*
+ * Section 4.1, "Orthogonalized JL transform": the sketch of qjl_make_sketch
+ * (same seed, same Gaussian draws) with its rows orthogonalised by QR.  Rows
+ * are taken in blocks of d (m > d rows cannot all be orthogonal); inside a
+ * block row i becomes the i-th Gram-Schmidt direction of the block's rows,
+ * scaled back to the length the Gaussian row had, so that each row is still
+ * N(0, I) by itself.  float64 arithmetic, rounded to float32 and then to
+ * `dtype`.  d <= 128.  A drop-in replacement for the sketch in every other
+ * call.
+ */
+int qjl_make_sketch_orthogonal(uint64_t seed, int m, int d, int dtype, void* S, void* stream);
+
+/*
  * Algorithm 1 steps 3-4 for all keys at once (Definition 3.1 Eq. (3)):
  *   bits [B,Hkv,n,m/8] (uint8)  <- packed sign(S k)
  *   norms[B,Hkv,n]     (binary16 bit patterns) <- ||k||_2

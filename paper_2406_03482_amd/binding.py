@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
     L.qjl_status_string.argtypes = [ctypes.c_int]
     L.qjl_make_sketch.restype = ctypes.c_int
     L.qjl_make_sketch.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    L.qjl_make_sketch_orthogonal.restype = ctypes.c_int
+    L.qjl_make_sketch_orthogonal.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     L.qjl_quantize_keys.restype = ctypes.c_int
     L.qjl_quantize_keys.argtypes = [sp, vp, vp, vp, vp, vp]
     L.qjl_project_query.restype = ctypes.c_int
@@ -118,6 +120,15 @@ def qjl_make_sketch(seed: int, m: int, d: int, dtype: torch.dtype = torch.bfloat
     S = torch.empty((m, d), dtype=dtype, device=device)
     _check("qjl_make_sketch",
            lib().qjl_make_sketch(seed & (2 ** 64 - 1), m, d, _tag(S), _dev(S, "S"), _stream(S)))
+    return S
+
+
+def qjl_make_sketch_orthogonal(seed: int, m: int, d: int, dtype: torch.dtype = torch.bfloat16,
+                               device="cuda") -> torch.Tensor:
+    """The sketch of qjl_make_sketch(seed, ...) with the rows of every block of d rows orthogonalised."""
+    S = torch.empty((m, d), dtype=dtype, device=device)
+    _check("qjl_make_sketch_orthogonal",
+           lib().qjl_make_sketch_orthogonal(seed & (2 ** 64 - 1), m, d, _tag(S), _dev(S, "S"), _stream(S)))
     return S
 
 

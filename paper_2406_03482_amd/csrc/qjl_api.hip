@@ -46,6 +46,12 @@ int qjl_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, void* strea
   return launch_make_sketch(seed, m, d, dtype, S, static_cast<hipStream_t>(stream));
 }
 
+int qjl_make_sketch_orthogonal(uint64_t seed, int m, int d, int dtype, void* S, void* stream) {
+  if (m < 1 || d < 1 || !dtype_ok(dtype) || !ptr_ok(S)) return QJL_ERR_INVALID_ARG;
+  if ((long)m * d > (1L << 31)) return QJL_ERR_UNSUPPORTED;
+  return launch_make_sketch_orthogonal(seed, m, d, dtype, S, static_cast<hipStream_t>(stream));
+}
+
 int qjl_quantize_keys(const qjl_shape* shape, const void* K, const void* S, uint8_t* bits,
                       uint16_t* norms, void* stream) {
   int rc = check_shape(shape);

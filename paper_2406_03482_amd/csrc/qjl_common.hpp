@@ -133,6 +133,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Launchers implemented one per source file; all validation is done by the
 // caller in qjl_api.hip.
 int launch_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, hipStream_t st);
+int launch_make_sketch_orthogonal(uint64_t seed, int m, int d, int dtype, void* S, hipStream_t st);
 int launch_quantize(const qjl_shape& sh, const void* K, const void* S, uint8_t* bits,
                     uint16_t* norms, hipStream_t st);
 int launch_quantize_dual(const qjl_shape& sh, int m_out, const void* K, const void* S_dual,

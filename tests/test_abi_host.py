@@ -32,7 +32,7 @@ def test_header_symbols_are_exported(L):
     names = _declared_symbols()
     assert names == ["qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
                      "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_workspace_bytes",
-                     "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_outlier_workspace_bytes",
+                     "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_make_sketch_orthogonal", "qjl_outlier_workspace_bytes",
                      "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_quantize_values",
                      "qjl_scores", "qjl_select_outliers", "qjl_status_string", "qjl_version"]
     for n in names:
@@ -177,3 +177,13 @@ def test_value_cache_entry_points_validate_on_the_host(L):
     assert L.qjl_decode_attention_vq(ctypes.byref(f32), 4, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
     assert L.qjl_decode_attention_vq(ctypes.byref(sh), 4, ok, ok, ok, ok, vp(None), ok, ok, ok, ok,
                                      ctypes.c_size_t(1 << 30), None, None, None) == INVALID
+
+
+def test_orthogonal_sketch_entry_point_validates_on_the_host(L):
+    ok = ctypes.c_void_p(0x1000)
+    L.qjl_make_sketch_orthogonal.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_void_p, ctypes.c_void_p]
+    assert L.qjl_make_sketch_orthogonal(1, 0, 128, 2, ok, None) == INVALID
+    assert L.qjl_make_sketch_orthogonal(1, 256, 128, 7, ok, None) == INVALID
+    assert L.qjl_make_sketch_orthogonal(1, 256, 128, 2, None, None) == INVALID
+    assert L.qjl_make_sketch_orthogonal(1, 256, 256, 2, ok, None) == UNSUPPORTED      # a block must fit in LDS

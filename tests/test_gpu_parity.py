@@ -435,3 +435,55 @@ def test_many_small_units():
     ref_sc = orc.estimate_scores(SQ32, bits, nu16, scale)
     rms = np.sqrt(np.mean(ref_sc ** 2, axis=-1, keepdims=True))
     assert np.all(np.abs(sc - ref_sc) <= 2e-3 * np.maximum(np.abs(ref_sc), 1e-2 * rms))
+
+
+# ------------------------------------------------------------------ orthogonalised sketch (Section 4.1)
+@pytest.mark.parametrize("dt", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("m,d,seed", [(256, 128, 2), (512, 128, 4), (128, 128, 9), (100, 128, 5), (40, 24, 99), (300, 128, 6)])
+def test_orthogonal_sketch_matches_oracle(dt, m, d, seed):
+    """Both sides orthogonalise the same Gaussian draws in float64 (Gram-Schmidt twice here, Householder QR in the
+    oracle); after rounding to the storage type the matrices must agree to the last bit almost everywhere, and
+    nowhere by more than one unit in the last place."""
+    say(f"[orth sketch] dt={dt} m={m} d={d} seed={seed}")
+    S = qjl.qjl_make_sketch_orthogonal(seed, m, d, DT[dt], DEV)
+    got = inputs.to_f64(S)
+    ref = orc.orthogonal_sketch(seed, m, d, dt)
+    same = float(np.mean(got == ref))
+    ulp = {"f32": 2.0 ** -23, "bf16": 2.0 ** -7, "f16": 2.0 ** -10}[dt]
+    worst = float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-30)))
+    say(f"  identical entries: {same:.6f}, worst relative difference {worst:.3g}")
+    assert same >= 0.999 and worst <= 1.01 * ulp
+    # structure, independent of the oracle: float32 storage keeps the rows of a block orthogonal to rounding
+    if dt == "f32":
+        for r0 in range(0, m, d):
+            Sb = got[r0:r0 + d]
+            gram = Sb @ Sb.T
+            off = gram - np.diag(np.diag(gram))
+            assert np.max(np.abs(off)) <= 1e-4
+    assert torch.equal(S, qjl.qjl_make_sketch_orthogonal(seed, m, d, DT[dt], DEV))
+
+
+def test_orthogonal_sketch_is_a_drop_in_and_lowers_the_error():
+    """The whole path runs unchanged on the orthogonalised sketch, and on the same data its attention output is
+    closer to exact attention (Section 4.1 reports that it almost always helps)."""
+    B, H, n, d, m, scale = 1, 8, 4096, 128, 256, 0.0884
+    K = inputs.make_keys(B, H, n, d, torch.bfloat16, 91, DEV, outliers=0)
+    Q = inputs.make_normal((B, H, d), torch.bfloat16, 92, DEV)
+    V = inputs.make_normal((B, H, n, d), torch.bfloat16, 93, DEV)
+    K64, Q64, V64 = inputs.to_f64(K), inputs.to_f64(Q), inputs.to_f64(V)
+    exact = orc.attention_from_scores(scale * np.einsum("bhd,bhnd->bhn", Q64, K64), V64)
+    errs = {}
+    for name, make in (("iid", qjl.qjl_make_sketch), ("orthogonal", qjl.qjl_make_sketch_orthogonal)):
+        tot = 0.0
+        for seed in range(6):
+            S = make(100 + seed, m, d, torch.bfloat16, DEV)
+            bits, norms = qjl.qjl_quantize_keys(K, S)
+            out = qjl.qjl_decode_attention(Q, S, bits, norms, V, scale).cpu().numpy().astype(np.float64)
+            if seed == 0:      # parity of the path on this sketch
+                rb, rn, _ = orc.quantize_keys(K64, inputs.to_f64(S))
+                ref = orc.decode_attention(Q64, inputs.to_f64(S), rb, rn, V64, scale)
+                assert np.max(np.abs(out - ref)) <= 2e-3
+            tot += float(np.mean((out - exact) ** 2))
+        errs[name] = (tot / 6) ** 0.5
+    say(f"[orth drop-in] rms error to exact attention: iid {errs['iid']:.4f}, orthogonalised {errs['orthogonal']:.4f}")
+    assert errs["orthogonal"] < errs["iid"]
