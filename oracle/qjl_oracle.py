@@ -73,6 +73,13 @@ Readings of points the paper leaves open (all restated where they are used):
     matrix are independent, so every row is still N(0, I) on its own and
     Lemma 3.2 holds unchanged; only rows of the same block are now orthogonal.
     Pinned by tests/test_oracle_orth_pins.py.
+  * Streaming (Algorithm 1's loop over the token stream): a key is quantized
+    when it arrives and appended to the cache; the estimator then runs over
+    the keys stored so far.  `decode_step` is one iteration in a cache of
+    fixed capacity: row `pos` receives the new key's code and norm, attention
+    covers rows 0..pos.  Rows are quantized independently, so streaming must
+    give exactly what quantizing all keys at once gives
+    (tests/test_oracle_stream_pins.py).
 
 Array conventions (all dense, C order):
     K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
@@ -433,3 +440,25 @@ def orthogonal_sketch(seed: int, m: int, d: int, dtype: str = "f32") -> np.ndarr
         Qt = Qt * np.sign(np.diag(R))[None, :]              # Gram-Schmidt's choice of sign: R_ii > 0
         S[r0:r0 + d] = np.linalg.norm(Gb, axis=1)[:, None] * Qt.T
     return S if dtype == "f64" else round_to_storage(S, dtype)
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1 as a stream: append one key, then estimate over the keys so far
+# --------------------------------------------------------------------------
+def append_keys(bits: np.ndarray, nu16: np.ndarray, K_new: np.ndarray, S: np.ndarray, pos: int):
+    """Algorithm 1 steps 3-4 for the tokens K_new [B,Hkv,t,d] arriving at positions pos..pos+t-1 of caches
+    bits [B,Hkv,cap,m/8], nu16 [B,Hkv,cap] (modified in place and returned)."""
+    t = K_new.shape[2]
+    if pos < 0 or pos + t > bits.shape[2]:
+        raise ValueError("append outside the cache")
+    b_new, nu_new, _ = quantize_keys(K_new, S)
+    bits[:, :, pos:pos + t] = b_new
+    nu16[:, :, pos:pos + t] = nu_new
+    return bits, nu16
+
+
+def decode_step(Q, S, bits, nu16, V, K_new, pos: int, scale: float = 1.0) -> np.ndarray:
+    """One generation step: the new token's key K_new [B,Hkv,1,d] is quantized into row `pos` of the caches, then
+    attention runs over rows 0..pos (V must already hold the new token's value in row pos)."""
+    append_keys(bits, nu16, K_new, S, pos)
+    return decode_attention(Q, S, bits[:, :, :pos + 1], nu16[:, :, :pos + 1], np.asarray(V)[:, :, :pos + 1], scale)
