@@ -104,6 +104,7 @@ def prepare_decode(qjl, inputs, w, dev):
         torch.cuda.synchronize()
         return dict(Q=Q, S=S, bits=bits, norms=norms, norms_out=norms_out, V=V, ws=ws, out=out)
     bits, norms = qjl.qjl_quantize_keys(K, S)       # untimed: the cache already exists at decode time
+    k_last = K[:, :, -1:].contiguous() if w.stream else None
     del K
     if w.vbits:                                     # value cache quantized token-wise (Section 3.2), also untimed
         vc, vs, vz = qjl.qjl_quantize_values(V, w.vbits)
@@ -115,10 +116,14 @@ def prepare_decode(qjl, inputs, w, dev):
                      dtype=torch.uint8, device=dev)
     out = torch.empty((w.batch, w.q_heads, w.d), dtype=torch.float32, device=dev)
     torch.cuda.synchronize()
-    return dict(Q=Q, S=S, bits=bits, norms=norms, V=V, ws=ws, out=out, **extra_v)
+    return dict(Q=Q, S=S, bits=bits, norms=norms, V=V, ws=ws, out=out, k_last=k_last, **extra_v)
 
 
 def run_decode(qjl, t, w, events=None):
+    if w.stream:        # the newest key is quantized into the last row, then attention over the full cache
+        qjl.qjl_decode_step(t["Q"], t["k_last"], t["S"], t["bits"], t["norms"], t["V"], w.n - 1, w.scale,
+                            out=t["out"], workspace=t["ws"])
+        return
     if w.vbits:
         qjl.qjl_decode_attention_vq(t["Q"], t["S"], t["bits"], t["norms"], t["vcodes"], t["vscale"], t["vzero"],
                                     w.vbits, w.scale, out=t["out"], workspace=t["ws"], events=events)
@@ -164,6 +169,8 @@ def time_decode(qjl, ev, w, t, steps, warmup, graph_batch=None):
         g.replay()
     torch.cuda.synchronize()
     ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    if w.stream:        # no kernel-timestamp variant of this call: the roofline figure uses the whole step
+        return dict(ms_graph=ms_graph, ms_eager=ms_eager, kernel_ms=ms_graph, kernel_ms_median=ms_graph, graph_batch=gb)
     # ---- the attention kernel alone: events recorded around it inside the library call
     nk = min(steps, 200)
     pairs = [(ev.create(), ev.create()) for _ in range(nk)]
@@ -326,7 +333,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
                     "metric is quoted on), c3, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
-                    "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache), for profiling single kernels; "
+                    "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache), c2s (append + decode), for profiling single kernels; "
                     "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -397,7 +404,8 @@ def main() -> int:
         for name, steps, warm in [("c3_long_context_b4_32k", 100, 20), ("c5a_llama3_8b_gqa_b1_128k", 200, 20),
                                   ("c5b_llama3_8b_gqa_b16_8k", 200, 20), ("c2d_llama2_7b_decode_4k_dual", 400, 40),
                                   ("c3d_long_context_b4_32k_dual", 100, 20), ("c2v_llama2_7b_decode_4k_v4", 400, 40),
-                                  ("c3v_long_context_b4_32k_v4", 100, 20), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20)]:
+                                  ("c3v_long_context_b4_32k_v4", 100, 20), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20),
+                                  ("c2s_llama2_7b_decode_step_4k", 400, 40)]:
             wx = inputs.WORKLOADS[name]
             tx = prepare_decode(qjl, inputs, wx, dev)
             extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm)))
@@ -409,7 +417,7 @@ def main() -> int:
         line["setup_kernels"] = bench_sketches(qjl, ev, dev)
         line["other_workloads"] = extra
 
-    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out and not w.vbits:
+    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out and not w.vbits and not w.stream:
         line["cpu_baseline"] = cpu_baseline(inputs, w)
     else:
         line["cpu_baseline"] = None

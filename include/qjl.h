@@ -257,6 +257,32 @@ int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, co
                             void* workspace, size_t workspace_bytes, void* stream,
                             void* event_before, void* event_after);
 
+/* ------------------------------------------------------------------------
+ * Streaming (Algorithm 1's loop over the token stream): a key is quantized
+ * when it arrives and appended to the cache; the estimator runs over the keys
+ * stored so far.  In these calls shape->n is the capacity of the caches
+ * (rows per (batch, kv head) of bits, norms and V).
+ * ---------------------------------------------------------------------- */
+
+/*
+ * Algorithm 1 steps 3-4 for `count` new tokens: K_new[B,Hkv,count,d] ->
+ * rows pos..pos+count-1 of bits[B,Hkv,n,m/8] and norms[B,Hkv,n]; other rows are
+ * not touched.  0 <= pos, pos + count <= n.  d == 128.
+ */
+int qjl_append_keys(const qjl_shape* shape, int pos, int count, const void* K_new, const void* S,
+                    uint8_t* bits, uint16_t* norms, void* stream);
+
+/*
+ * One generation step: K_new[B,Hkv,1,d] is quantized into row `pos` of the
+ * caches, then out[B,Hq,d] <- attention of Q[B,Hq,d] over rows 0..pos
+ * (Algorithm 1 EstimateScores + Eq. (1)).  Row `pos` of V[B,Hkv,n,d] must
+ * already hold the new token's value.  Workspace:
+ * qjl_decode_workspace_bytes(shape) covers every pos.
+ */
+int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const void* Q, const void* S,
+                    uint8_t* bits, uint16_t* norms, const void* V, float* out, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -82,6 +82,10 @@ def lib() -> ctypes.CDLL:
     L.qjl_quantize_values.argtypes = [sp, ip, vp, vp, vp, vp, vp]
     L.qjl_decode_attention_vq.restype = ctypes.c_int
     L.qjl_decode_attention_vq.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    L.qjl_append_keys.restype = ctypes.c_int
+    L.qjl_append_keys.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp]
+    L.qjl_decode_step.restype = ctypes.c_int
+    L.qjl_decode_step.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -370,4 +374,41 @@ def qjl_decode_attention_vq(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor
                                          _dev(vzero, "vzero"), _dev(out, "out"), _dev(workspace, "workspace"),
                                          workspace.numel() * workspace.element_size(), _stream(Q),
                                          events[0] if events else None, events[1] if events else None))
+    return out
+
+
+# ---- streaming (Algorithm 1 as a loop over the token stream)
+def qjl_append_keys(K_new: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor, pos: int) -> None:
+    """K_new[B,Hkv,t,d] -> rows pos..pos+t-1 of bits[B,Hkv,cap,m/8], norms[B,Hkv,cap] (in place)."""
+    B, Hkv, t, d = K_new.shape
+    m = S.shape[0]
+    cap = bits.shape[2]
+    if tuple(bits.shape) != (B, Hkv, cap, m // 8) or tuple(norms.shape) != (B, Hkv, cap) or S.dtype != K_new.dtype:
+        raise ValueError("caches do not match K_new and S")
+    sh = _shape(B, Hkv, Hkv, cap, d, m, _tag(K_new))
+    _check("qjl_append_keys",
+           lib().qjl_append_keys(ctypes.byref(sh), pos, t, _dev(K_new, "K_new"), _dev(S, "S"), _dev(bits, "bits"),
+                                 _dev(norms, "norms"), _stream(K_new)))
+
+
+def qjl_decode_step(Q: torch.Tensor, K_new: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor,
+                    V: torch.Tensor, pos: int, scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Append K_new[B,Hkv,1,d] at row pos, then attention of Q[B,Hq,d] over rows 0..pos -> float32 [B,Hq,d]."""
+    B, Hq, d = Q.shape
+    _, Hkv, cap, _ = V.shape
+    m = S.shape[0]
+    if tuple(K_new.shape) != (B, Hkv, 1, d) or tuple(bits.shape) != (B, Hkv, cap, m // 8):
+        raise ValueError("K_new must be [B,Hkv,1,d]; bits [B,Hkv,cap,m/8]")
+    need = qjl_decode_workspace_bytes(B, Hq, Hkv, cap, d, m, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, cap, d, m, _tag(Q), scale)
+    _check("qjl_decode_step",
+           lib().qjl_decode_step(ctypes.byref(sh), pos, _dev(K_new, "K_new"), _dev(Q, "Q"), _dev(S, "S"),
+                                 _dev(bits, "bits"), _dev(norms, "norms"), _dev(V, "V"), _dev(out, "out"),
+                                 _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                 _stream(Q)))
     return out

@@ -106,7 +106,7 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
   if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
 }
@@ -176,7 +176,7 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
   if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, nullptr, nullptr, out,
+  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, nullptr, nullptr, 0, out,
                        workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
@@ -207,9 +207,41 @@ int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, co
   if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, vcodes, vscale, vzero, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, vcodes, vscale, vzero, 0, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
+}
+
+int qjl_append_keys(const qjl_shape* shape, int pos, int count, const void* K_new, const void* S,
+                    uint8_t* bits, uint16_t* norms, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(K_new) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms)) return QJL_ERR_INVALID_ARG;
+  if (pos < 0 || count < 1 || (long)pos + count > shape->n) return QJL_ERR_INVALID_ARG;
+  if (shape->d != 128 || shape->m % 32 != 0) return QJL_ERR_UNSUPPORTED;
+  if ((long)shape->batch * shape->kv_heads * count > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
+  return launch_append_keys(*shape, K_new, count, pos, S, bits, norms, static_cast<hipStream_t>(stream));
+}
+
+int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const void* Q, const void* S,
+                    uint8_t* bits, uint16_t* norms, const void* V, float* out, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(K_new) || !ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(V) || !ptr_ok(out))
+    return QJL_ERR_INVALID_ARG;
+  if (pos < 0 || pos >= shape->n) return QJL_ERR_INVALID_ARG;
+  qjl_shape now = *shape;                          // attention covers rows 0..pos of caches with shape->n rows
+  now.n = pos + 1;
+  decode_plan plan;
+  if (!plan_decode(now, 0, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  rc = launch_append_keys(*shape, K_new, 1, pos, S, bits, norms, st);
+  if (rc != QJL_OK) return rc;
+  return launch_decode(now, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, shape->n, out, workspace, st,
+                       nullptr, nullptr);
 }
 
 }  // extern "C"

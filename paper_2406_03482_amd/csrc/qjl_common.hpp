@@ -165,8 +165,11 @@ struct decode_plan {
 bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  const uint16_t* vscale, const uint16_t* vzero, float* out, void* workspace,
+                  const uint16_t* vscale, const uint16_t* vzero, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
+// n_cap: rows per (batch, kv head) in bits / norms / V (0: exactly sh.n, the number of keys attended to).
+int launch_append_keys(const qjl_shape& sh, const void* K_new, int t, int pos, const void* S, uint8_t* bits,
+                       uint16_t* norms, hipStream_t st);
 int device_cu_count();
 
 }  // namespace qjl

@@ -47,7 +47,8 @@ struct decode_args {
   const uint16_t* vzero;
   float* part;            // [B,Hq,nsplit,132]
   float* out;             // [B,Hq,128]
-  int n, groups_per_kv;
+  int n, groups_per_kv;   // n = keys to attend to
+  long n_cap;             // rows per (batch, kv head) in the caches (>= n; larger for a cache that is still filling)
   int nsplit, chunk;
   float coef2;            // scale * sqrt(pi/2) / m * log2(e); m = bits of the (first) code part
   float coef2b;           // the same for the second part
@@ -198,7 +199,7 @@ decode_kernel(decode_args a) {
 
   const int k_begin = split * a.chunk;
   const int k_end = min(a.n, k_begin + a.chunk);
-  const size_t row0 = (size_t)bk * a.n;
+  const size_t row0 = (size_t)bk * a.n_cap;         // first row of this (batch, kv head) in the caches
   float* pbuf = pbuf_all + wave * 64 * GT;
   int r = lane >> 4;                                  // row of a 4-row V pass
   const int c = lane & 15;                            // 8-channel slice
@@ -599,7 +600,7 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
 
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  const uint16_t* vscale, const uint16_t* vzero, float* out, void* workspace,
+                  const uint16_t* vscale, const uint16_t* vzero, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
@@ -612,6 +613,7 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.part = reinterpret_cast<float*>(ws + plan.off_part);
   a.out = out;
   a.n = sh.n;
+  a.n_cap = n_cap > 0 ? n_cap : sh.n;
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;

@@ -36,6 +36,7 @@ class Workload:
     outliers: int = 4
     m_out: int = 0          # > 0: outlier channels get a second sketch of m_out rows (m is the inlier sketch)
     vbits: int = 0          # > 0: the value cache is quantized token-wise to vbits bits per entry
+    stream: bool = False    # a generation step: the last key is quantized and appended, then attention runs
 
     @property
     def key_heads(self) -> int:
@@ -65,6 +66,8 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("c2v_llama2_7b_decode_4k_v4", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, vbits=4),
     Workload("c3v_long_context_b4_32k_v4", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=4),
     Workload("c5bv_llama3_8b_gqa_b16_8k_v4", 16, 32, 8, 8192, 128, 256, torch.bfloat16, _RS, 1006, 5, vbits=4),
+    # a whole generation step on the headline shape: append the newest key (Algorithm 1's loop), then attend
+    Workload("c2s_llama2_7b_decode_step_4k", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, stream=True),
 ]}
 
 

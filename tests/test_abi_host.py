@@ -30,8 +30,9 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(L):
     names = _declared_symbols()
-    assert names == ["qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
-                     "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_workspace_bytes",
+    assert names == ["qjl_append_keys", "qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
+                     "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_step",
+                     "qjl_decode_workspace_bytes",
                      "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_make_sketch_orthogonal", "qjl_outlier_workspace_bytes",
                      "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_quantize_values",
                      "qjl_scores", "qjl_select_outliers", "qjl_status_string", "qjl_version"]
@@ -187,3 +188,16 @@ def test_orthogonal_sketch_entry_point_validates_on_the_host(L):
     assert L.qjl_make_sketch_orthogonal(1, 256, 128, 7, ok, None) == INVALID
     assert L.qjl_make_sketch_orthogonal(1, 256, 128, 2, None, None) == INVALID
     assert L.qjl_make_sketch_orthogonal(1, 256, 256, 2, ok, None) == UNSUPPORTED      # a block must fit in LDS
+
+
+def test_streaming_entry_points_validate_on_the_host(L):
+    sh = QJLShape(1, 4, 2, 100, 128, 256, 2, 1.0)
+    ok = ctypes.c_void_p(0x1000)
+    assert L.qjl_append_keys(ctypes.byref(sh), -1, 1, ok, ok, ok, ok, None) == INVALID
+    assert L.qjl_append_keys(ctypes.byref(sh), 99, 2, ok, ok, ok, ok, None) == INVALID        # past the capacity
+    assert L.qjl_append_keys(ctypes.byref(sh), 0, 0, ok, ok, ok, ok, None) == INVALID
+    assert L.qjl_append_keys(ctypes.byref(sh), 0, 1, None, ok, ok, ok, None) == INVALID
+    d64 = QJLShape(1, 4, 2, 100, 64, 256, 2, 1.0)
+    assert L.qjl_append_keys(ctypes.byref(d64), 0, 1, ok, ok, ok, ok, None) == UNSUPPORTED
+    assert L.qjl_decode_step(ctypes.byref(sh), 100, ok, ok, ok, ok, ok, ok, ok, ok, ctypes.c_size_t(1 << 30), None) == INVALID
+    assert L.qjl_decode_step(ctypes.byref(sh), 5, ok, ok, ok, ok, ok, ok, ok, None, ctypes.c_size_t(0), None) == WORKSPACE

@@ -487,3 +487,55 @@ def test_orthogonal_sketch_is_a_drop_in_and_lowers_the_error():
         errs[name] = (tot / 6) ** 0.5
     say(f"[orth drop-in] rms error to exact attention: iid {errs['iid']:.4f}, orthogonalised {errs['orthogonal']:.4f}")
     assert errs["orthogonal"] < errs["iid"]
+
+
+# ------------------------------------------------------------------ streaming (Algorithm 1 as a loop)
+@pytest.mark.parametrize("dt,B,Hkv,t,m,pos", [("bf16", 2, 3, 1, 256, 5), ("bf16", 1, 32, 1, 256, 4095), ("f16", 1, 2, 7, 512, 0),
+                                              ("f32", 1, 1, 3, 128, 10), ("bf16", 1, 2, 4, 192, 1), ("bf16", 1, 8, 64, 384, 36)])
+def test_append_keys_parity(dt, B, Hkv, t, m, pos):
+    say(f"[append] dt={dt} B={B} Hkv={Hkv} t={t} m={m} pos={pos}")
+    d, cap = 128, pos + t + 3
+    K_new = inputs.make_keys(B, Hkv, t, d, DT[dt], 200 + t, DEV, outliers=4)
+    S = qjl.qjl_make_sketch(5, m, d, DT[dt], DEV)
+    bits = torch.full((B, Hkv, cap, m // 8), 0xA5, dtype=torch.uint8, device=DEV)
+    norms = torch.full((B, Hkv, cap), 77.0, dtype=torch.float16, device=DEV)
+    qjl.qjl_append_keys(K_new, S, bits, norms, pos)
+    torch.cuda.synchronize()
+    K64, S64 = inputs.to_f64(K_new), inputs.to_f64(S)
+    bad, flips, inband = bits_report(bits[:, :, pos:pos + t].cpu().numpy(), K64, S64)
+    say(f"  bits: {bad} mismatches outside the band, {flips} flips among {inband} near-zero entries")
+    assert bad == 0
+    assert_norms(norms[:, :, pos:pos + t].cpu().numpy(), K64)
+    untouched = torch.ones(cap, dtype=torch.bool); untouched[pos:pos + t] = False
+    assert torch.all(bits[:, :, untouched.to(DEV)] == 0xA5) and torch.all(norms[:, :, untouched.to(DEV)] == 77.0)
+    # the bulk quantizer and the append kernel agree on every bit of these keys outside the near-zero band
+    b2, n2 = qjl.qjl_quantize_keys(K_new, S)
+    bad2, _, _ = bits_report(b2.cpu().numpy(), K64, S64)
+    assert bad2 == 0
+
+
+def test_decode_steps_stream_into_a_cache():
+    """Eight generation steps from a prefilled cache: after every step the cache rows and the attention output
+    match the oracle's stream, which in turn equals quantizing everything at once."""
+    B, Hq, Hkv, cap, d, m, scale, n0 = 1, 8, 4, 300, 128, 256, 0.0884, 292
+    K = inputs.make_keys(B, Hkv, cap, d, torch.bfloat16, 301, DEV, outliers=4)
+    V = inputs.make_normal((B, Hkv, cap, d), torch.bfloat16, 302, DEV)
+    Qs = inputs.make_normal((cap, B * Hq, d), torch.bfloat16, 303, DEV).view(cap, B, Hq, d)
+    S = qjl.qjl_make_sketch(6, m, d, torch.bfloat16, DEV)
+    K64, V64, S64 = inputs.to_f64(K), inputs.to_f64(V), inputs.to_f64(S)
+    rb, rn, _ = orc.quantize_keys(K64[:, :, :n0], S64)                       # the oracle's prefill
+    ob = np.zeros((B, Hkv, cap, m // 8), dtype=np.uint8); on = np.zeros((B, Hkv, cap), dtype=np.float16)
+    ob[:, :, :n0] = rb; on[:, :, :n0] = rn
+    bits = torch.from_numpy(ob.copy()).to(DEV); norms = torch.from_numpy(on.copy()).to(DEV)
+    ws = torch.empty((qjl.qjl_decode_workspace_bytes(B, Hq, Hkv, cap, d, m, torch.bfloat16),), dtype=torch.uint8, device=DEV)
+    worst = 0.0
+    for pos in range(n0, cap):
+        out = qjl.qjl_decode_step(Qs[pos].contiguous(), K[:, :, pos:pos + 1].contiguous(), S, bits, norms, V, pos, scale, workspace=ws)
+        ref = orc.decode_step(inputs.to_f64(Qs[pos]), S64, ob, on, V64, K64[:, :, pos:pos + 1], pos, scale)
+        bad, _, _ = bits_report(bits[:, :, pos:pos + 1].cpu().numpy(), K64[:, :, pos:pos + 1], S64)
+        assert bad == 0
+        bits[:, :, pos] = torch.from_numpy(ob[:, :, pos]).to(DEV)          # keep both sides on the oracle's code
+        norms[:, :, pos] = torch.from_numpy(on[:, :, pos]).to(DEV)
+        worst = max(worst, assert_attention(out.cpu().numpy(), ref))
+    say(f"[stream] worst attention error over {cap - n0} steps: {worst:.3g}")
+    assert torch.all(bits[:, :, :n0].cpu() == torch.from_numpy(ob[:, :, :n0]))   # earlier rows never rewritten
