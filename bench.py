@@ -318,7 +318,7 @@ def cpu_baseline(inputs, w, budget_s=12.0):
             orc.decode_attention(Q64, S, bits, nu16, V64, w.scale)
             reps += 1
             el = time.perf_counter() - t0
-            if el >= budget_s or reps >= 50:
+            if el >= budget_s or reps >= 500:
                 break
         used = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": w.key_heads * reps / el, "unit": "keys/s", "cores": int(min(cores, used)), "kind": "oracle",

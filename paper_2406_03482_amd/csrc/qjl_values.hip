@@ -6,7 +6,8 @@
 // that zero + code * scale is the nearest representable value.  b = 4 here.
 //
 // The code is an integer decided by floating point: subtract, divide and round
-// are IEEE float32 operations in exactly this order.
+// are IEEE float32 operations in exactly this order (the kernel takes a shortcut
+// only where it provably gives the same integer).
 #include "qjl_common.hpp"
 
 namespace qjl {
@@ -33,9 +34,17 @@ value_quant4_kernel(const void* __restrict__ V, uint32_t* __restrict__ codes,
     const float sc = f16_bits_to_float(s16), z = f16_bits_to_float(z16);
     uint32_t word = 0;
     if (sc > 0.f) {
+      // rint((x - z) / sc) without a division per entry: q0 = rint((x - z) * (1/sc)) is right whenever
+      // the remainder (x - z) - q0 * sc (exact: one fused multiply-add) is clear of half a step; the
+      // rounding of the quotient moves it by < 2^-19 steps, the margin is 2^-18.  The few entries
+      // near a tie take the division itself, so every code is the one the definition gives.
+      const float inv = 1.0f / sc;
+      const float clear = (0.5f - 0x1.0p-18f) * sc;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float q = rintf((x[e] - z) / sc);
+        const float t = x[e] - z;
+        float q = rintf(t * inv);
+        if (!(fabsf(fmaf(-q, sc, t)) < clear)) q = rintf(t / sc);
         q = fminf(fmaxf(q, 0.f), 15.f);
         word |= (uint32_t)q << (4 * e);
       }

@@ -140,3 +140,19 @@ def test_full_size_vq_sampled(name, units):
     worst = max(float(np.max(np.abs(out[b, g:g + 1].astype(np.float64) - ref))) for (b, g), ref in refs.items())
     say(f"  worst attention error over {len(refs)} heads: {worst:.3g}")
     assert worst <= 2e-3 and np.all(np.isfinite(out))
+
+
+def test_quantize_values_on_rows_full_of_ties():
+    """Rows whose entries sit exactly on, or one bf16 step away from, the midpoints between codes: the kernel's
+    division-free shortcut must hand every such entry to the exact path."""
+    V = torch.zeros((1, 4, 4096, 128), dtype=torch.bfloat16, device=DEV)
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    V[0, 0] = (torch.arange(128, device=DEV).float() % 31 * 0.25).to(torch.bfloat16)          # scale 0.5: every second entry is a tie
+    V[0, 1] = (torch.randint(0, 61, (4096, 128), device=DEV, generator=g).float() * 0.125).to(torch.bfloat16)
+    V[0, 2] = (torch.randn((4096, 128), device=DEV, generator=g) * 3).to(torch.bfloat16)
+    V[0, 3] = (torch.randint(-40, 41, (4096, 128), device=DEV, generator=g).float() * 0.0625).to(torch.bfloat16)
+    codes, sc, z = qjl.qjl_quantize_values(V, 4)
+    rc, rs, rz = orc.quantize_values(inputs.to_f64(V), 4)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), rs.view(np.uint16))
+    assert np.array_equal(z.cpu().numpy().view(np.uint16), rz.view(np.uint16))
+    assert int((codes.cpu().numpy() != rc).sum()) == 0
