@@ -241,7 +241,7 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
         "ms_per_step": ms,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": load_traffic(w.name),
-                     "kernel": "quantize_mfma_kernel", "kernel_ms": ms, "flops": flops,
+                     "kernel": "quantize_slds_kernel" if mt <= 512 else "quantize_mfma_kernel", "kernel_ms": ms, "flops": flops,
                      "algorithmic_bytes": algo_bytes, "hbm_GBs": algo_bytes / (ms * 1e-3) / 1e9},
     }
 

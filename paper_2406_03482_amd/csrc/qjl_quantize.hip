@@ -1,14 +1,20 @@
 // Algorithm 1 steps 3-4 / Definition 3.1 Eq. (3): for every key store the packed
 // sign bits of S k and the norm ||k||_2.
 //
-// Two paths:
+// Three paths:
 //  * 16-bit keys with d = 128 and m a multiple of 128: K S^T is a dense
 //    contraction and runs on the matrix cores (v_mfma_f32_32x32x16, fp32
-//    accumulation).  Each wave keeps its share of S in registers for the whole
-//    kernel; key tiles stream HBM -> registers -> LDS once, the norm is taken
-//    on the way, and the accumulators are reduced to bits in registers, so the
-//    projections never reach memory.
+//    accumulation); the accumulators are reduced to bits in registers, so the
+//    projections never reach memory, and the norm is taken from the same
+//    registers that feed the MFMAs.
+//      - m <= 512: the sketch lives in LDS, every wave works on key tiles of
+//        its own (quantize_slds_kernel);
+//      - larger m: each wave keeps its share of S in registers for the whole
+//        kernel and the four waves of a workgroup share key tiles staged in
+//        LDS (quantize_mfma_kernel).
 //  * anything else (fp32 keys, other d or m): plain fp32 FMA loops.
+#include <type_traits>
+
 #include "qjl_common.hpp"
 
 namespace qjl {
@@ -42,6 +48,8 @@ constexpr int kRowU4 = 17;      // LDS row pitch in 16-byte units: 256 B of key 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 // sum of squares of the eight 16-bit elements of one 16-byte chunk, fp32 accumulation
 // (v_dot2_f32_bf16 / v_dot2_f32_f16: two products and the add per instruction)
 template <typename T> __device__ __forceinline__ float sumsq8(const uint4& u);
@@ -60,6 +68,11 @@ template <> __device__ __forceinline__ float sumsq8<f16_t>(const uint4& u) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_fdot2(p[i], p[i], s, false);
   return s;
+}
+
+template <typename T> __device__ __forceinline__ float sumsq8v(const u32x4& v) {
+  uint4 u = make_uint4(v[0], v[1], v[2], v[3]);
+  return sumsq8<T>(u);
 }
 
 // Sign extraction: v_alignbit(t, acc, 31) shifts the IEEE sign bit of an accumulator
@@ -297,6 +310,258 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   }
 }
 
+// ---------------------------------------------------------------- sketch in LDS, keys in registers
+// For m <= 512 the whole sketch fits in the CU's LDS (m rows of 256 B + 16 B pad).
+// Then the roles swap: S is the MFMA A operand read from LDS, a wave's 64 keys
+// are the B operands and stay in its registers (lane (h, j): key j, elements
+// 16s + 8h .. 16s + 8h + 7 of step s).  Keys are fetched as whole 128-byte
+// lines one tile ahead and rearranged into that layout through 2 KB of LDS
+// private to the wave.  A wave owns its keys from load to store: after the one
+// barrier behind the copy of S no wave ever waits for another, and the two
+// waves of a SIMD fill the matrix pipe for each other while one of them
+// rearranges keys, takes norms, extracts bits or stores.
+//
+// LDS row (b, rho) of block b holds projection ((rho>>2)&1)*m/2 + 16b + 4(rho>>3) + (rho&3):
+// accumulator register v of lane (h, j) is then code bit h*m/2 + 16b + v of
+// key j, and after all NB = m/32 blocks lane (h, j) holds m/2 consecutive code
+// bits of its key -- m/16 contiguous bytes, stored from registers.
+constexpr int kSPitch = 17;     // LDS pitch of a sketch row in 16-byte units
+
+// f(integral_constant<int, I>) for I = 0 .. N-1: indices that are constants to the compiler front end
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+template <typename T, int NB, bool DUAL>
+__global__ void __launch_bounds__(512, 1)
+quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S, size_t seg_stride,
+                     uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
+                     uint16_t* __restrict__ norms_out, const int32_t* __restrict__ channels, int count,
+                     long rows, int num_tiles, int seg0) {
+  using frag = typename mma<T>::frag;
+  constexpr int m = NB * 32;
+  constexpr int NW = NB / 2;              // code words a lane holds per key
+  extern __shared__ uint4 sbuf[];         // [m][kSPitch]
+  {
+    const size_t seg = (size_t)seg0 + blockIdx.z;
+    K += seg * (size_t)rows * 128;
+    S += seg * seg_stride;
+    bits += seg * (size_t)rows * (size_t)NB;
+    norms += seg * (size_t)rows;
+    if constexpr (DUAL) {
+      norms_out += seg * (size_t)rows;
+      channels += seg * (size_t)count;
+    }
+  }
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int h = lane >> 5;
+  const int j = lane & 31;
+
+  for (int idx = tid; idx < m * 16; idx += 512) {
+    const int lr = idx >> 4, c = idx & 15;
+    const int b = lr >> 5, rho = lr & 31;
+    const int srow = ((rho >> 2) & 1) * (m / 2) + 16 * b + 4 * (rho >> 3) + (rho & 3);
+    sbuf[lr * kSPitch + c] = *reinterpret_cast<const uint4*>(S + (size_t)srow * 128 + c * 8);
+  }
+
+  // DUAL: which of this lane's 64 elements are outlier channels.  Bit 8s + e of
+  // omask = element 16s + 8h + e; smask (uniform) = steps with any such element.
+  uint64_t omask = 0;
+  uint32_t smask = 0;
+  if constexpr (DUAL) {
+    for (int t = 0; t < count; ++t) {
+      const int c = min(max(channels[t], 0), 127);
+      smask |= 1u << (c >> 4);
+      if (((c >> 3) & 1) == h) omask |= 1ull << (8 * (c >> 4) + (c & 7));
+    }
+  }
+
+  // Keys leave HBM in whole 128-byte lines: load p = 4*nb + 2*kh + ... covers eight
+  // keys (lane >> 3) and one half row (chunks 8*kh + (lane & 7)); a wave's private
+  // 2 KB of LDS turns 16 keys x 128 bytes at a time into the MFMA layout.
+  // pre[2*g + q], g = 4*nb + 2*kh + half: keys 32*nb + 16*half + 8*q + (lane >> 3).
+  u32x4 pre[16];
+  const int lrow = lane >> 3, lchk = lane & 7;
+  const uint32_t koff = (uint32_t)(lrow * 128 + lchk * 8);
+  auto load_tile = [&](int wt) {
+    const long row0 = (long)wt * kTok;
+    if (row0 + kTok <= rows) {            // uniform: whole tile inside K
+      const uint16_t* kp = K + (size_t)row0 * 128;
+      static_for<0, 16>([&](auto pc) {
+        constexpr int p = decltype(pc)::value, g = p >> 1, q = p & 1;
+        constexpr int key = 32 * (g >> 2) + 16 * (g & 1) + 8 * q, kh = (g >> 1) & 1;
+        pre[p] = *reinterpret_cast<const u32x4*>(kp + (koff + (uint32_t)(key * 128 + kh * 64)));
+      });
+    } else {
+      static_for<0, 16>([&](auto pc) {
+        constexpr int p = decltype(pc)::value, g = p >> 1, q = p & 1;
+        constexpr int key = 32 * (g >> 2) + 16 * (g & 1) + 8 * q, kh = (g >> 1) & 1;
+        long row = row0 + key + lrow;
+        if (row >= rows) row = rows - 1;  // clamp: stay inside K, results of such rows are dropped
+        pre[p] = *reinterpret_cast<const u32x4*>(K + (size_t)row * 128 + kh * 64 + lchk * 8);
+      });
+    }
+  };
+
+  // Tiles are handed out inside the workgroup: it owns a contiguous range, the
+  // first eight go to its waves in order, every further one to whichever wave
+  // asks next.  (Of the two waves of a SIMD the older one wins the matrix pipe,
+  // so equal shares fixed in advance would leave the younger ones running alone
+  // at the end.)
+  uint32_t* next_tile = reinterpret_cast<uint32_t*>(sbuf + m * kSPitch);
+  u32x4* stage = reinterpret_cast<u32x4*>(sbuf + m * kSPitch + 1 + wave * 128);    // this wave's 16 keys x 8 chunks
+  const int per_wg = (num_tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int tile0 = blockIdx.x * per_wg;
+  const int ntile = min(per_wg, num_tiles - tile0);      // may be <= 0 for the last workgroups
+  if (tid == 0) *next_tile = 8u;
+  int wt = wave;                          // index inside the workgroup's range
+  if (wt < ntile) load_tile(tile0 + wt);
+  __syncthreads();                        // S is in LDS; the only barrier of the kernel
+  auto grab_tile = [&]() {
+    uint32_t v = 0;
+    if (lane == 0) v = atomicAdd(next_tile, 1u);
+    return (int)__builtin_amdgcn_readfirstlane(v);
+  };
+  const int abase = j * kSPitch + h;
+
+  // lane (h, j) holds words h*NW .. h*NW + NW - 1 of the code rows of keys j and 32 + j
+  uint32_t code[2][NW];
+  auto store_codes = [&](int tile) {
+    const long r0 = (long)tile * kTok;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const long row = r0 + nb * 32 + j;
+      if (row < rows) {
+        uint32_t* dst = bits + (size_t)row * NB + h * NW;
+        if constexpr (NW % 4 == 0) {
+#pragma unroll
+          for (int q = 0; q < NW / 4; ++q)
+            reinterpret_cast<uint4*>(dst)[q] =
+                make_uint4(code[nb][4 * q], code[nb][4 * q + 1], code[nb][4 * q + 2], code[nb][4 * q + 3]);
+        } else {
+#pragma unroll
+          for (int q = 0; q < NW / 2; ++q)
+            reinterpret_cast<uint2*>(dst)[q] = make_uint2(code[nb][2 * q], code[nb][2 * q + 1]);
+        }
+      }
+    }
+  };
+
+  int done = -1;                          // tile whose code words wait in registers
+  while (wt < ntile) {
+    // cur[nb][s]: key 32*nb + j, chunk 2s + h.  Chunk c of staged row r sits at
+    // r*8 + (c ^ ((r >> 1) & 7)): the 16 lanes of a write (two rows) and of a read
+    // (16 rows, one chunk) then touch every bank once.
+    u32x4 cur[2][8];
+    static_for<0, 8>([&](auto gc) {
+      constexpr int g = decltype(gc)::value;
+      stage[lrow * 8 + (lchk ^ ((lrow >> 1) & 7))] = pre[2 * g];
+      stage[(lrow + 8) * 8 + (lchk ^ (((lrow + 8) >> 1) & 7))] = pre[2 * g + 1];
+      __builtin_amdgcn_wave_barrier();
+      if ((j >> 4) == (g & 1)) {
+        const int r = j & 15;
+        static_for<0, 4>([&](auto sc) {
+          constexpr int s = decltype(sc)::value;
+          cur[g >> 2][4 * ((g >> 1) & 1) + s] = stage[r * 8 + ((2 * s + h) ^ ((r >> 1) & 7))];
+        });
+      }
+      __builtin_amdgcn_wave_barrier();
+    });
+    // The previous tile's code leaves only now: memory operations complete in
+    // issue order, so stores issued behind the prefetch would have to be
+    // waited for together with it.
+    if (done >= 0) store_codes(done);
+    // the next tile's keys travel while this one is computed (past the end: the
+    // range's last tile again, so that the loop body has no load behind a branch)
+    const int wt_next = grab_tile();
+    load_tile(tile0 + min(wt_next, ntile - 1));
+
+    const long row0 = (long)(tile0 + wt) * kTok;
+    // ---- norms: a key's elements are split over lanes (0, j) and (1, j)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      float ss = 0.f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) ss += sumsq8v<T>(cur[nb][s]);
+      ss += __shfl_xor(ss, 32);
+      const long row = row0 + nb * 32 + j;
+      if constexpr (DUAL) {
+        float so = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+          if ((smask >> s) & 1u) {                    // uniform
+            const uint32_t mb = (uint32_t)(omask >> (8 * s)) & 0xFFu;
+            const uint32_t w[4] = {cur[nb][s][0], cur[nb][s][1], cur[nb][s][2], cur[nb][s][3]};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              float a, b;
+              unpack2<T>(w[i], a, b);
+              so = fmaf(a, ((mb >> (2 * i)) & 1u) ? a : 0.f, so);
+              so = fmaf(b, ((mb >> (2 * i + 1)) & 1u) ? b : 0.f, so);
+            }
+          }
+        }
+        so += __shfl_xor(so, 32);
+        if (h == 0 && row < rows) norms_out[row] = float_to_f16_bits(sqrtf(so));
+        ss = fmaxf(ss - so, 0.f);
+      }
+      if (h == 0 && row < rows) norms[row] = float_to_f16_bits(sqrtf(ss));
+    }
+
+    // ---- MFMA phase: unit u = block u of 32 projections against both key
+    // sub-tiles (two accumulator chains of 8 MFMAs), then its 2 x 16 sign bits.
+    // The A operand of step g+2 is fetched from LDS while step g runs; the
+    // SIMD's other wave fills the matrix pipe while this one extracts bits.
+    auto lds_a = [&](int g) {
+      frag f;
+      const uint4 u4 = sbuf[abase + (g >> 3) * (32 * kSPitch) + 2 * (g & 7)];
+      __builtin_memcpy(&f, &u4, 16);
+      return f;
+    };
+    auto key_b = [&](int nb, int s) {
+      frag f;
+      __builtin_memcpy(&f, &cur[nb][s], 16);
+      return f;
+    };
+    constexpr int kSteps = NB * 8;
+    frag aq[3];
+    aq[0] = lds_a(0);
+    aq[1] = lds_a(1);
+    const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      f32x16_t acc[2];
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const int g = u * 8 + s;
+        if (g + 2 < kSteps) aq[(g + 2) % 3] = lds_a(g + 2);
+        acc[0] = mma<T>::run(aq[g % 3], key_b(0, s), s == 0 ? zero : acc[0]);
+        acc[1] = mma<T>::run(aq[g % 3], key_b(1, s), s == 0 ? zero : acc[1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {               // bit v = [acc[v] >= 0]
+        uint32_t tb = 0u;
+#pragma unroll
+        for (int v = 15; v >= 0; --v) tb = __builtin_amdgcn_alignbit(tb, __float_as_uint(acc[c][v]), 31);
+        asm volatile("" : "+v"(tb));              // the bits are taken here, not where they are stored
+        if (u % 2 == 0) code[c][u / 2] = (~tb) & 0xFFFFu;
+        else code[c][u / 2] |= (~tb) << 16;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    done = tile0 + wt;
+    wt = wt_next;
+  }
+  if (done >= 0) store_codes(done);
+}
+
 // ---------------------------------------------------------------- generic fp32-FMA path
 constexpr int kGenTok = 8;
 
@@ -373,8 +638,44 @@ int launch_mfma(const quant_io& q, hipStream_t st) {
   return launch_status();
 }
 
+template <typename T, int NB, bool DUAL>
+int launch_slds(const quant_io& q, hipStream_t st) {
+  const long tiles = (q.rows + kTok - 1) / kTok;
+  if (tiles > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
+  // the sketch, the tile counter, 2 KB per wave to rearrange keys
+  constexpr size_t lds = (size_t)NB * 32 * kSPitch * 16 + 16 + 8 * 2048;
+  static bool attr_set = false;           // the kernel needs more than the default 64 KB of LDS
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_slds_kernel<T, NB, DUAL>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_status(e);
+    attr_set = true;
+  }
+  // one workgroup of eight waves per CU in total, each owning a range of its segment's tiles
+  long gx = (device_cu_count() + q.segments - 1) / q.segments;
+  if (gx > (tiles + 7) / 8) gx = (tiles + 7) / 8;
+  for (long s0 = 0; s0 < q.segments; s0 += 65535) {
+    const long nz = q.segments - s0 < 65535 ? q.segments - s0 : 65535;
+    dim3 grid((unsigned)gx, 1u, (unsigned)nz);
+    hipLaunchKernelGGL((quantize_slds_kernel<T, NB, DUAL>), grid, dim3(512), lds, st,
+                       static_cast<const uint16_t*>(q.K), static_cast<const uint16_t*>(q.S), q.seg_stride,
+                       reinterpret_cast<uint32_t*>(q.bits), q.norms, q.norms_out, q.channels, q.count,
+                       q.rows, (int)tiles, (int)s0);
+  }
+  return launch_status();
+}
+
 template <typename T, bool DUAL>
 int launch_mfma_m(const quant_io& q, hipStream_t st) {
+  if (q.rows > 0) {
+    switch (q.m) {                        // the whole sketch fits in LDS
+      case 128: return launch_slds<T, 4, DUAL>(q, st);
+      case 256: return launch_slds<T, 8, DUAL>(q, st);
+      case 384: return launch_slds<T, 12, DUAL>(q, st);
+      case 512: return launch_slds<T, 16, DUAL>(q, st);
+      default: break;
+    }
+  }
   if (q.m % 512 == 0) return launch_mfma<T, 128, DUAL, 4>(q, st);
   if (q.m % 384 == 0) return launch_mfma<T, 128, DUAL, 3>(q, st);   // one pass over the keys instead of three
   if (q.m % 256 == 0) return launch_mfma<T, 64, DUAL, 4>(q, st);
