@@ -38,6 +38,19 @@ template <> struct mma<f16_t> {
   }
 };
 
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <typename T> struct mma16;
+template <> struct mma16<bf16_t> {
+  static __device__ __forceinline__ f32x4_t run(bf16x8_t a, bf16x8_t b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct mma16<f16_t> {
+  static __device__ __forceinline__ f32x4_t run(f16x8_t a, f16x8_t b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+};
+
 template <typename T> __device__ __forceinline__ float elem_to_float(uint16_t x);
 template <> __device__ __forceinline__ float elem_to_float<bf16_t>(uint16_t x) { return bf16_bits_to_float(x); }
 template <> __device__ __forceinline__ float elem_to_float<f16_t>(uint16_t x) { return f16_bits_to_float(x); }
@@ -313,18 +326,12 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
 // ---------------------------------------------------------------- sketch in LDS, keys in registers
 // For m <= 512 the whole sketch fits in the CU's LDS (m rows of 256 B + 16 B pad).
 // Then the roles swap: S is the MFMA A operand read from LDS, a wave's 64 keys
-// are the B operands and stay in its registers (lane (h, j): key j, elements
-// 16s + 8h .. 16s + 8h + 7 of step s).  Keys are fetched as whole 128-byte
-// lines one tile ahead and rearranged into that layout through 2 KB of LDS
-// private to the wave.  A wave owns its keys from load to store: after the one
-// barrier behind the copy of S no wave ever waits for another, and the two
-// waves of a SIMD fill the matrix pipe for each other while one of them
-// rearranges keys, takes norms, extracts bits or stores.
-//
-// LDS row (b, rho) of block b holds projection ((rho>>2)&1)*m/2 + 16b + 4(rho>>3) + (rho&3):
-// accumulator register v of lane (h, j) is then code bit h*m/2 + 16b + v of
-// key j, and after all NB = m/32 blocks lane (h, j) holds m/2 consecutive code
-// bits of its key -- m/16 contiguous bytes, stored from registers.
+// are the B operands and stay in its registers.  Keys are fetched as whole
+// 128-byte lines one tile ahead and rearranged into the MFMA layout through
+// 2 KB of LDS private to the wave.  A wave owns its keys from load to store:
+// after the one barrier behind the copy of S no wave ever waits for another,
+// and the two waves of a SIMD fill the matrix pipe for each other while one of
+// them rearranges keys, takes norms or stores.
 constexpr int kSPitch = 17;     // LDS pitch of a sketch row in 16-byte units
 
 // f(integral_constant<int, I>) for I = 0 .. N-1: indices that are constants to the compiler front end
@@ -335,15 +342,26 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
   }
 }
 
+// v_mfma_f32_16x16x32: a unit is 16 projections against four sub-tiles of 16
+// keys (four accumulator chains of four MFMAs, 4 registers each), so two sets
+// of accumulators fit and the sign bits of unit u-1 are taken between the MFMAs
+// of unit u (one v_alignbit per accumulator register).  Lane (q, j) =
+// (lane >> 4, lane & 15): A row / key j, elements 32s + 8q .. 32s + 8q + 7 of
+// step s; accumulator register v is projection row 4q + v of the unit.  LDS
+// row (b, rho) holds projection (rho>>2)*m/4 + 32(b>>3) + 4(7 - (b&7)) + (rho&3):
+// shifting one bit per register into a word, units in order, leaves lane (q, j)
+// with m/4 consecutive code bits of key j -- m/32 contiguous bytes, stored from
+// registers.
 template <typename T, int NB, bool DUAL>
 __global__ void __launch_bounds__(512, 1)
 quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict__ S, size_t seg_stride,
-                     uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
-                     uint16_t* __restrict__ norms_out, const int32_t* __restrict__ channels, int count,
-                     long rows, int num_tiles, int seg0) {
+                       uint32_t* __restrict__ bits, uint16_t* __restrict__ norms,
+                       uint16_t* __restrict__ norms_out, const int32_t* __restrict__ channels, int count,
+                       long rows, int num_tiles, int seg0) {
   using frag = typename mma<T>::frag;
   constexpr int m = NB * 32;
-  constexpr int NW = NB / 2;              // code words a lane holds per key
+  constexpr int NU = m / 16;              // units
+  constexpr int NW = NB / 4;              // code words a lane holds per key
   extern __shared__ uint4 sbuf[];         // [m][kSPitch]
   {
     const size_t seg = (size_t)seg0 + blockIdx.z;
@@ -359,32 +377,29 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int h = lane >> 5;
-  const int j = lane & 31;
+  const int q = lane >> 4;
+  const int j = lane & 15;
 
   for (int idx = tid; idx < m * 16; idx += 512) {
     const int lr = idx >> 4, c = idx & 15;
-    const int b = lr >> 5, rho = lr & 31;
-    const int srow = ((rho >> 2) & 1) * (m / 2) + 16 * b + 4 * (rho >> 3) + (rho & 3);
+    const int b = lr >> 4, rho = lr & 15;
+    const int srow = (rho >> 2) * (m / 4) + 32 * (b >> 3) + 4 * (7 - (b & 7)) + (rho & 3);
     sbuf[lr * kSPitch + c] = *reinterpret_cast<const uint4*>(S + (size_t)srow * 128 + c * 8);
   }
 
-  // DUAL: which of this lane's 64 elements are outlier channels.  Bit 8s + e of
-  // omask = element 16s + 8h + e; smask (uniform) = steps with any such element.
-  uint64_t omask = 0;
+  // DUAL: which of this lane's 32 elements are outlier channels.  Bit 8s + e of
+  // omask = element 32s + 8q + e; smask (uniform) = steps with any such element.
+  uint32_t omask = 0;
   uint32_t smask = 0;
   if constexpr (DUAL) {
     for (int t = 0; t < count; ++t) {
       const int c = min(max(channels[t], 0), 127);
-      smask |= 1u << (c >> 4);
-      if (((c >> 3) & 1) == h) omask |= 1ull << (8 * (c >> 4) + (c & 7));
+      smask |= 1u << (c >> 5);
+      if (((c >> 3) & 3) == q) omask |= 1u << (8 * (c >> 5) + (c & 7));
     }
   }
 
-  // Keys leave HBM in whole 128-byte lines: load p = 4*nb + 2*kh + ... covers eight
-  // keys (lane >> 3) and one half row (chunks 8*kh + (lane & 7)); a wave's private
-  // 2 KB of LDS turns 16 keys x 128 bytes at a time into the MFMA layout.
-  // pre[2*g + q], g = 4*nb + 2*kh + half: keys 32*nb + 16*half + 8*q + (lane >> 3).
+  // pre[2*g + p], g = 2*c + kh: keys 16*c + 8*p + (lane >> 3), chunks 8*kh + (lane & 7)
   u32x4 pre[16];
   const int lrow = lane >> 3, lchk = lane & 7;
   const uint32_t koff = (uint32_t)(lrow * 128 + lchk * 8);
@@ -393,14 +408,14 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     if (row0 + kTok <= rows) {            // uniform: whole tile inside K
       const uint16_t* kp = K + (size_t)row0 * 128;
       static_for<0, 16>([&](auto pc) {
-        constexpr int p = decltype(pc)::value, g = p >> 1, q = p & 1;
-        constexpr int key = 32 * (g >> 2) + 16 * (g & 1) + 8 * q, kh = (g >> 1) & 1;
+        constexpr int p = decltype(pc)::value, g = p >> 1;
+        constexpr int key = 16 * (g >> 1) + 8 * (p & 1), kh = g & 1;
         pre[p] = *reinterpret_cast<const u32x4*>(kp + (koff + (uint32_t)(key * 128 + kh * 64)));
       });
     } else {
       static_for<0, 16>([&](auto pc) {
-        constexpr int p = decltype(pc)::value, g = p >> 1, q = p & 1;
-        constexpr int key = 32 * (g >> 2) + 16 * (g & 1) + 8 * q, kh = (g >> 1) & 1;
+        constexpr int p = decltype(pc)::value, g = p >> 1;
+        constexpr int key = 16 * (g >> 1) + 8 * (p & 1), kh = g & 1;
         long row = row0 + key + lrow;
         if (row >= rows) row = rows - 1;  // clamp: stay inside K, results of such rows are dropped
         pre[p] = *reinterpret_cast<const u32x4*>(K + (size_t)row * 128 + kh * 64 + lchk * 8);
@@ -408,11 +423,6 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     }
   };
 
-  // Tiles are handed out inside the workgroup: it owns a contiguous range, the
-  // first eight go to its waves in order, every further one to whichever wave
-  // asks next.  (Of the two waves of a SIMD the older one wins the matrix pipe,
-  // so equal shares fixed in advance would leave the younger ones running alone
-  // at the end.)
   uint32_t* next_tile = reinterpret_cast<uint32_t*>(sbuf + m * kSPitch);
   u32x4* stage = reinterpret_cast<u32x4*>(sbuf + m * kSPitch + 1 + wave * 128);    // this wave's 16 keys x 8 chunks
   const int per_wg = (num_tiles + (int)gridDim.x - 1) / (int)gridDim.x;
@@ -427,26 +437,24 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     if (lane == 0) v = atomicAdd(next_tile, 1u);
     return (int)__builtin_amdgcn_readfirstlane(v);
   };
-  const int abase = j * kSPitch + h;
+  const int abase = j * kSPitch + q;
 
-  // lane (h, j) holds words h*NW .. h*NW + NW - 1 of the code rows of keys j and 32 + j
-  uint32_t code[2][NW];
+  // lane (q, j) holds words q*NW .. q*NW + NW - 1 of the code rows of keys 16*c + j
+  uint32_t code[4][NW];
   auto store_codes = [&](int tile) {
     const long r0 = (long)tile * kTok;
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const long row = r0 + nb * 32 + j;
+    for (int c = 0; c < 4; ++c) {
+      const long row = r0 + c * 16 + j;
       if (row < rows) {
-        uint32_t* dst = bits + (size_t)row * NB + h * NW;
-        if constexpr (NW % 4 == 0) {
-#pragma unroll
-          for (int q = 0; q < NW / 4; ++q)
-            reinterpret_cast<uint4*>(dst)[q] =
-                make_uint4(code[nb][4 * q], code[nb][4 * q + 1], code[nb][4 * q + 2], code[nb][4 * q + 3]);
+        uint32_t* dst = bits + (size_t)row * NB + q * NW;
+        if constexpr (NW == 4) {
+          *reinterpret_cast<uint4*>(dst) = make_uint4(code[c][0], code[c][1], code[c][2], code[c][3]);
+        } else if constexpr (NW == 2) {
+          *reinterpret_cast<uint2*>(dst) = make_uint2(code[c][0], code[c][1]);
         } else {
 #pragma unroll
-          for (int q = 0; q < NW / 2; ++q)
-            reinterpret_cast<uint2*>(dst)[q] = make_uint2(code[nb][2 * q], code[nb][2 * q + 1]);
+          for (int w = 0; w < NW; ++w) dst[w] = code[c][w];
         }
       }
     }
@@ -454,49 +462,40 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
 
   int done = -1;                          // tile whose code words wait in registers
   while (wt < ntile) {
-    // cur[nb][s]: key 32*nb + j, chunk 2s + h.  Chunk c of staged row r sits at
-    // r*8 + (c ^ ((r >> 1) & 7)): the 16 lanes of a write (two rows) and of a read
-    // (16 rows, one chunk) then touch every bank once.
-    u32x4 cur[2][8];
+    // cur[c][s]: key 16*c + j, chunk 4s + q
+    u32x4 cur[4][4];
     static_for<0, 8>([&](auto gc) {
       constexpr int g = decltype(gc)::value;
       stage[lrow * 8 + (lchk ^ ((lrow >> 1) & 7))] = pre[2 * g];
       stage[(lrow + 8) * 8 + (lchk ^ (((lrow + 8) >> 1) & 7))] = pre[2 * g + 1];
       __builtin_amdgcn_wave_barrier();
-      if ((j >> 4) == (g & 1)) {
-        const int r = j & 15;
-        static_for<0, 4>([&](auto sc) {
-          constexpr int s = decltype(sc)::value;
-          cur[g >> 2][4 * ((g >> 1) & 1) + s] = stage[r * 8 + ((2 * s + h) ^ ((r >> 1) & 7))];
-        });
-      }
+      static_for<0, 2>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        cur[g >> 1][2 * (g & 1) + t] = stage[j * 8 + ((4 * t + q) ^ ((j >> 1) & 7))];
+      });
       __builtin_amdgcn_wave_barrier();
     });
-    // The previous tile's code leaves only now: memory operations complete in
-    // issue order, so stores issued behind the prefetch would have to be
-    // waited for together with it.
-    if (done >= 0) store_codes(done);
-    // the next tile's keys travel while this one is computed (past the end: the
-    // range's last tile again, so that the loop body has no load behind a branch)
+    if (done >= 0) store_codes(done);     // behind the wait for this tile's keys, before the next prefetch
     const int wt_next = grab_tile();
     load_tile(tile0 + min(wt_next, ntile - 1));
 
     const long row0 = (long)(tile0 + wt) * kTok;
-    // ---- norms: a key's elements are split over lanes (0, j) and (1, j)
+    // ---- norms: a key's elements are split over lanes (0..3, j)
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int c = 0; c < 4; ++c) {
       float ss = 0.f;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) ss += sumsq8v<T>(cur[nb][s]);
+      for (int s = 0; s < 4; ++s) ss += sumsq8v<T>(cur[c][s]);
+      ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      const long row = row0 + nb * 32 + j;
+      const long row = row0 + c * 16 + j;
       if constexpr (DUAL) {
         float so = 0.f;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
+        for (int s = 0; s < 4; ++s) {
           if ((smask >> s) & 1u) {                    // uniform
-            const uint32_t mb = (uint32_t)(omask >> (8 * s)) & 0xFFu;
-            const uint32_t w[4] = {cur[nb][s][0], cur[nb][s][1], cur[nb][s][2], cur[nb][s][3]};
+            const uint32_t mb = (omask >> (8 * s)) & 0xFFu;
+            const uint32_t w[4] = {cur[c][s][0], cur[c][s][1], cur[c][s][2], cur[c][s][3]};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               float a, b;
@@ -506,55 +505,61 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
             }
           }
         }
+        so += __shfl_xor(so, 16);
         so += __shfl_xor(so, 32);
-        if (h == 0 && row < rows) norms_out[row] = float_to_f16_bits(sqrtf(so));
+        if (q == 0 && row < rows) norms_out[row] = float_to_f16_bits(sqrtf(so));
         ss = fmaxf(ss - so, 0.f);
       }
-      if (h == 0 && row < rows) norms[row] = float_to_f16_bits(sqrtf(ss));
+      if (q == 0 && row < rows) norms[row] = float_to_f16_bits(sqrtf(ss));
     }
 
-    // ---- MFMA phase: unit u = block u of 32 projections against both key
-    // sub-tiles (two accumulator chains of 8 MFMAs), then its 2 x 16 sign bits.
-    // The A operand of step g+2 is fetched from LDS while step g runs; the
-    // SIMD's other wave fills the matrix pipe while this one extracts bits.
+    // ---- MFMA phase
     auto lds_a = [&](int g) {
       frag f;
-      const uint4 u4 = sbuf[abase + (g >> 3) * (32 * kSPitch) + 2 * (g & 7)];
+      const uint4 u4 = sbuf[abase + (g >> 2) * (16 * kSPitch) + 4 * (g & 3)];
       __builtin_memcpy(&f, &u4, 16);
       return f;
     };
-    auto key_b = [&](int nb, int s) {
+    auto key_b = [&](int c, int s) {
       frag f;
-      __builtin_memcpy(&f, &cur[nb][s], 16);
+      __builtin_memcpy(&f, &cur[c][s], 16);
       return f;
     };
-    constexpr int kSteps = NB * 8;
+    constexpr int kSteps = NU * 4;
     frag aq[3];
     aq[0] = lds_a(0);
     aq[1] = lds_a(1);
-    const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t acc[2][4];
+    uint32_t tb[4] = {0u, 0u, 0u, 0u};
+    static_for<0, NU + 1>([&](auto uc) {          // round NU only drains the last unit's bits
+      constexpr int u = decltype(uc)::value, par = u & 1;
+      static_for<0, 4>([&](auto sc) {
+        constexpr int s = decltype(sc)::value, g = u * 4 + s;
+        if constexpr (g + 2 < kSteps) aq[(g + 2) % 3] = lds_a(g + 2);
+        if constexpr (u < NU) {
 #pragma unroll
-    for (int u = 0; u < NB; ++u) {
-      f32x16_t acc[2];
+          for (int c = 0; c < 4; ++c)
+            acc[par][c] = mma16<T>::run(aq[g % 3], key_b(c, s), s == 0 ? zero : acc[par][c]);
+        }
+        if constexpr (u > 0) {
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const int g = u * 8 + s;
-        if (g + 2 < kSteps) aq[(g + 2) % 3] = lds_a(g + 2);
-        acc[0] = mma<T>::run(aq[g % 3], key_b(0, s), s == 0 ? zero : acc[0]);
-        acc[1] = mma<T>::run(aq[g % 3], key_b(1, s), s == 0 ? zero : acc[1]);
+          for (int c = 0; c < 4; ++c)
+            tb[c] = __builtin_amdgcn_alignbit(tb[c], __float_as_uint(acc[par ^ 1][c][3 - s]), 31);
+        }
         __builtin_amdgcn_sched_barrier(0);
-      }
+      });
+      if constexpr (u > 0) {
 #pragma unroll
-      for (int c = 0; c < 2; ++c) {               // bit v = [acc[v] >= 0]
-        uint32_t tb = 0u;
-#pragma unroll
-        for (int v = 15; v >= 0; --v) tb = __builtin_amdgcn_alignbit(tb, __float_as_uint(acc[c][v]), 31);
-        asm volatile("" : "+v"(tb));              // the bits are taken here, not where they are stored
-        if (u % 2 == 0) code[c][u / 2] = (~tb) & 0xFFFFu;
-        else code[c][u / 2] |= (~tb) << 16;
+        for (int c = 0; c < 4; ++c) {
+          asm volatile("" : "+v"(tb[c]));           // the bits are taken here, not where they are stored
+          if constexpr ((u - 1) % 8 == 7) {         // bit = [acc >= 0]
+            code[c][(u - 1) / 8] = ~tb[c];
+            tb[c] = 0u;
+          }
+        }
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    });
 
     done = tile0 + wt;
     wt = wt_next;
