@@ -275,7 +275,7 @@ def bench_value_quantize(qjl, inputs, ev, w, dev, steps, warmup):
         "rows_per_s": rows / (ms * 1e-3),
         "ms_per_step": ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "value_quant4_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "value_quant_kernel",
                      "kernel_ms": ms, "algorithmic_bytes": algo_bytes},
     }
 
@@ -333,7 +333,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
                     "metric is quoted on), c3, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
-                    "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache), c2s (append + decode), for profiling single kernels; "
+                    "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache; c3v2, c3v8: 2 and 8 bits), c2s (append + decode), for profiling single kernels; "
                     "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")

@@ -240,7 +240,7 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
 
 /*
  * vcodes[B,Hkv,n,d*vbits/8], vscale[B,Hkv,n], vzero[B,Hkv,n] (binary16) <-
- * V[B,Hkv,n,d] of type shape->dtype.  Supported: vbits == 4, d == 128.
+ * V[B,Hkv,n,d] of type shape->dtype.  Supported: vbits in {2, 4, 8}, d == 128.
  */
 int qjl_quantize_values(const qjl_shape* shape, int vbits, const void* V, uint8_t* vcodes,
                         uint16_t* vscale, uint16_t* vzero, void* stream);
@@ -248,7 +248,7 @@ int qjl_quantize_values(const qjl_shape* shape, int vbits, const void* V, uint8_
 /*
  * qjl_decode_attention with the values taken from a cache written by
  * qjl_quantize_values: out[B,Hq,d] <- sum_j softmax_j(...) * (vzero[j] + vscale[j] * code[j,:]).
- * Supported: vbits == 4, d == 128, 16-bit shape->dtype (type of Q and S).
+ * Supported: vbits in {2, 4, 8}, d == 128, 16-bit shape->dtype (type of Q and S).
  * Workspace: qjl_decode_workspace_bytes(shape); events as in qjl_decode_attention_timed.
  */
 int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, const void* S,

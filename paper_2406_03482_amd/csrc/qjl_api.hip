@@ -106,7 +106,7 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
   if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, 0, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
 }
@@ -176,7 +176,7 @@ int qjl_decode_attention_dual(const qjl_shape* shape, int m_out, const void* Q, 
   if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, nullptr, nullptr, 0, out,
+  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, V, nullptr, nullptr, 0, 0, out,
                        workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
@@ -202,12 +202,12 @@ int qjl_decode_attention_vq(const qjl_shape* shape, int vbits, const void* Q, co
       !ptr_ok(vzero) || !ptr_ok(out))
     return QJL_ERR_INVALID_ARG;
   if (vbits < 1 || vbits > 8) return QJL_ERR_INVALID_ARG;
-  if (vbits != 4 || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
+  if ((vbits != 2 && vbits != 4 && vbits != 8) || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
   decode_plan plan;
   if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
-  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, vcodes, vscale, vzero, 0, out, workspace,
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, vcodes, vscale, vzero, vbits, 0, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
 }
@@ -240,7 +240,7 @@ int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const vo
   hipStream_t st = static_cast<hipStream_t>(stream);
   rc = launch_append_keys(*shape, K_new, 1, pos, S, bits, norms, st);
   if (rc != QJL_OK) return rc;
-  return launch_decode(now, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, shape->n, out, workspace, st,
+  return launch_decode(now, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, shape->n, out, workspace, st,
                        nullptr, nullptr);
 }
 

@@ -161,11 +161,11 @@ struct decode_plan {
 // m_out = 0: one code per key (sh.m bits, one shared sketch S[m,d]).  m_out > 0: a key's
 // code is sh.m + m_out bits of two independent instances with a norm each, and S
 // holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).  vscale != nullptr: V holds
-// 4-bit value codes with a binary16 scale and zero point per token.
+// vbits-bit value codes (2, 4 or 8) with a binary16 scale and zero point per token.
 bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  const uint16_t* vscale, const uint16_t* vzero, long n_cap, float* out, void* workspace,
+                  const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
 // n_cap: rows per (batch, kv head) in bits / norms / V (0: exactly sh.n, the number of keys attended to).
 int launch_append_keys(const qjl_shape& sh, const void* K_new, int t, int pos, const void* S, uint8_t* bits,

@@ -136,34 +136,64 @@ __device__ __forceinline__ float dot8(const slice8<f32_t>& s, const slice8<f32_t
 // channels) with its own norm; a.S then points to per-head sketches whose rows
 // are already restricted to the coordinates of each instance, so S q needs no
 // special case, and the two partial inner products are weighted separately.
-// ... or 4 bytes: eight 4-bit codes of a quantized value row (Section 3.2).  The
-// codes come out as floats 0..15; scale and zero point are applied per row.
-struct vtile_q4 {
+// ... or b bytes: eight b-bit codes of a quantized value row (Section 3.2), b = 2, 4
+// or 8.  The codes come out as floats 0 .. 2^b - 1; scale and zero point are
+// applied per row.  Every code is first moved into a byte of its own, then one
+// v_cvt_f32_ubyteN per code.  The conversions are written as asm because the
+// compiler otherwise extracts every code with its own bit-field instruction.
+__device__ __forceinline__ void bytes_to_floats(uint32_t even, uint32_t odd, float (&x)[8]) {
+  asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(even));
+  asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[1]) : "v"(odd));
+  asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[2]) : "v"(even));
+  asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[3]) : "v"(odd));
+  asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[4]) : "v"(even));
+  asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[5]) : "v"(odd));
+  asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[6]) : "v"(even));
+  asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[7]) : "v"(odd));
+}
+template <int BITS> struct vtile_q;
+template <> struct vtile_q<4> {
   uint32_t r;
   __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
     r = *reinterpret_cast<const uint32_t*>(static_cast<const char*>(V) + byte_off);
   }
-  // One code per byte, then one v_cvt_f32_ubyteN per code (11 instructions per
-  // row instead of 16).  The conversions are written as asm because the
-  // compiler otherwise extracts every code with its own bit-field instruction.
   __device__ __forceinline__ void get(float (&x)[8]) const {
-    const uint32_t even = r & 0x0F0F0F0Fu, odd = (r >> 4) & 0x0F0F0F0Fu;
-    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(even));
-    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[1]) : "v"(odd));
-    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[2]) : "v"(even));
-    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[3]) : "v"(odd));
-    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[4]) : "v"(even));
-    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[5]) : "v"(odd));
-    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[6]) : "v"(even));
-    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[7]) : "v"(odd));
+    bytes_to_floats(r & 0x0F0F0F0Fu, (r >> 4) & 0x0F0F0F0Fu, x);
+  }
+};
+template <> struct vtile_q<2> {
+  uint32_t r;
+  __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
+    r = *reinterpret_cast<const uint16_t*>(static_cast<const char*>(V) + byte_off);
+  }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    uint32_t t = (r | (r << 8)) & 0x00FF00FFu;      // the two code bytes, a byte apart
+    t = (t | (t << 4)) & 0x0F0F0F0Fu;               // byte i: codes 2i (low two bits) and 2i + 1
+    bytes_to_floats(t & 0x03030303u, (t >> 2) & 0x03030303u, x);
+  }
+};
+template <> struct vtile_q<8> {
+  uint2 r;
+  __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
+    r = *reinterpret_cast<const uint2*>(static_cast<const char*>(V) + byte_off);
+  }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(r.x));
+    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[1]) : "v"(r.x));
+    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[2]) : "v"(r.x));
+    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[3]) : "v"(r.x));
+    asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[4]) : "v"(r.y));
+    asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[5]) : "v"(r.y));
+    asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[6]) : "v"(r.y));
+    asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[7]) : "v"(r.y));
   }
 };
 
-// VQ: the values are stored as 4-bit codes with a binary16 scale and zero point
+// VB > 0: the values are stored as VB-bit codes with a binary16 scale and zero point
 // per token (Section 3.2).  o = sum_j p_j (zero_j + scale_j c_j): the weight
 // that goes to the value pass is p_j scale_j, and sum_j p_j zero_j, the same for
 // every channel, is carried next to the softmax denominator.
-template <typename T, int GT, int MW, int MWB, bool VQ>
+template <typename T, int GT, int MW, int MWB, int VB>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
                                   T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
@@ -231,7 +261,8 @@ decode_kernel(decode_args a) {
   // V rows in flight per lane: 16 (a whole 64-key block ahead), or 8 where the
   // four-head group needs the registers for its accumulators and tables
   constexpr int VD = GT == 4 ? 8 : 16;
-  using VT = typename std::conditional<VQ, vtile_q4, vtile<T>>::type;
+  constexpr bool VQ = VB > 0;
+  using VT = typename std::conditional<VQ, vtile_q<VQ ? VB : 4>, vtile<T>>::type;
   VT v[VD];
   // V loads requested before the tables are built: enough to keep HBM busy
   // meanwhile, few enough that the rows of S (requested just before them, and
@@ -242,8 +273,8 @@ decode_kernel(decode_args a) {
   auto issue_v = [&](int slot, int i, int kb, int last_row) {   // row pass i of block kb -> v[slot]
     const int rr = min(4 * i + r, last_row);
     if constexpr (VQ) {
-      const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD / 2);
-      v[slot].load(base, (uint32_t)(rr * (kD / 2) + c * 4));
+      const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * VB / 8);
+      v[slot].load(base, (uint32_t)(rr * (kD * VB / 8) + c * VB));
     } else {
       const char* base = static_cast<const char*>(a.V) + (row0 + kb) * (size_t)(kD * T::bytes);
       v[slot].load(base, (uint32_t)(rr * kD + c * 8));
@@ -475,14 +506,14 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
   if (half == 0) out[head * kD + ch] = (O + s_o[ch] + Zc + s_zsum) / (L + s_lsum);
 }
 
-template <typename T, int GT, int MW, int MWB, bool VQ>
+template <typename T, int GT, int MW, int MWB, int VB>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   static bool attr_set = false;
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
   const size_t lds = decode_lds_bytes(GT, MW * 32);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VQ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
@@ -491,34 +522,40 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
   if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
   if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
-    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VQ>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
                           ev0, ev1, 0u, a);
   else
-    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VQ>), grid, dim3(kNW * 64), lds, st, a);
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB>), grid, dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
-template <typename T, int MW, int MWB, bool VQ = false>
+template <typename T, int MW, int MWB, int VB = 0>
 int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   switch (plan.gt) {
-    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    default: return launch_t<T, 1, MW, MWB, VQ>(sh, plan, a, st, ev0, ev1);
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW, MWB, VB>(sh, plan, a, st, ev0, ev1);
   }
 }
 
 // m = bits of the (first) code part, m_out = bits of the second part (0: none)
 template <typename T>
-int launch_m(const qjl_shape& sh, int m_out, const decode_plan& plan, const decode_args& a, hipStream_t st,
+int launch_m(const qjl_shape& sh, int m_out, int vbits, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   if (a.vscale != nullptr) {                        // quantized values: 16-bit queries, one-part codes
     if constexpr (T::bytes == 2) {
       if (m_out != 0) return QJL_ERR_UNSUPPORTED;
-      switch (sh.m) {
-        case 128: return launch_g<T, 4, 0, true>(sh, plan, a, st, ev0, ev1);
-        case 256: return launch_g<T, 8, 0, true>(sh, plan, a, st, ev0, ev1);
-        case 512: return launch_g<T, 16, 0, true>(sh, plan, a, st, ev0, ev1);
+      switch (sh.m * 16 + vbits) {
+        case 128 * 16 + 2: return launch_g<T, 4, 0, 2>(sh, plan, a, st, ev0, ev1);
+        case 128 * 16 + 4: return launch_g<T, 4, 0, 4>(sh, plan, a, st, ev0, ev1);
+        case 128 * 16 + 8: return launch_g<T, 4, 0, 8>(sh, plan, a, st, ev0, ev1);
+        case 256 * 16 + 2: return launch_g<T, 8, 0, 2>(sh, plan, a, st, ev0, ev1);
+        case 256 * 16 + 4: return launch_g<T, 8, 0, 4>(sh, plan, a, st, ev0, ev1);
+        case 256 * 16 + 8: return launch_g<T, 8, 0, 8>(sh, plan, a, st, ev0, ev1);
+        case 512 * 16 + 2: return launch_g<T, 16, 0, 2>(sh, plan, a, st, ev0, ev1);
+        case 512 * 16 + 4: return launch_g<T, 16, 0, 4>(sh, plan, a, st, ev0, ev1);
+        case 512 * 16 + 8: return launch_g<T, 16, 0, 8>(sh, plan, a, st, ev0, ev1);
         default: return QJL_ERR_UNSUPPORTED;
       }
     } else {
@@ -600,7 +637,7 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
 
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
-                  const uint16_t* vscale, const uint16_t* vzero, long n_cap, float* out, void* workspace,
+                  const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
@@ -618,9 +655,9 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
   switch (sh.dtype) {
-    case QJL_F32: rc = launch_m<f32_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
-    case QJL_F16: rc = launch_m<f16_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
-    default: rc = launch_m<bf16_t>(sh, m_out, plan, a, st, ev_before, ev_after); break;
+    case QJL_F32: rc = launch_m<f32_t>(sh, m_out, vbits, plan, a, st, ev_before, ev_after); break;
+    case QJL_F16: rc = launch_m<f16_t>(sh, m_out, vbits, plan, a, st, ev_before, ev_after); break;
+    default: rc = launch_m<bf16_t>(sh, m_out, vbits, plan, a, st, ev_before, ev_after); break;
   }
   if (rc != QJL_OK || plan.nsplit == 1) return rc;
   // kernel 3: merge the chunks

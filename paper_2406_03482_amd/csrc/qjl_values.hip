@@ -3,7 +3,8 @@
 // scale = (max - min) / (2^b - 1), both stored as binary16; the code of an
 // entry is (v - zero) / scale rounded to the nearest integer (ties to even) and
 // clipped to [0, 2^b - 1], taken against the stored zero point and scale, so
-// that zero + code * scale is the nearest representable value.  b = 4 here.
+// that zero + code * scale is the nearest representable value.  b = 2, 4 or 8;
+// the first entry's code sits in the lowest bits of a byte.
 //
 // The code is an integer decided by floating point: subtract, divide and round
 // are IEEE float32 operations in exactly this order (the kernel takes a shortcut
@@ -14,12 +15,13 @@ namespace qjl {
 namespace {
 
 // d == 128: sixteen lanes share a row (8 entries each); minimum and maximum by
-// 16-lane DPP reductions; a lane packs its eight 4-bit codes into one word, so
-// a row's 64 code bytes leave as one contiguous piece.
-template <typename T>
+// 16-lane DPP reductions; a lane packs its eight b-bit codes into b bytes, so a
+// row's 16 b code bytes leave as one contiguous piece.
+template <typename T, int BITS>
 __global__ void __launch_bounds__(256)
-value_quant4_kernel(const void* __restrict__ V, uint32_t* __restrict__ codes,
-                    uint16_t* __restrict__ vscale, uint16_t* __restrict__ vzero, long rows) {
+value_quant_kernel(const void* __restrict__ V, uint8_t* __restrict__ codes,
+                   uint16_t* __restrict__ vscale, uint16_t* __restrict__ vzero, long rows) {
+  constexpr float kLevels = (float)((1 << BITS) - 1);
   const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
   for (long row = (long)blockIdx.x * 16 + r; row < rows; row += (long)gridDim.x * 16) {
     float x[8];
@@ -29,45 +31,65 @@ value_quant4_kernel(const void* __restrict__ V, uint32_t* __restrict__ codes,
     for (int e = 1; e < 8; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
     lo = row16_min(lo);
     hi = row16_max(hi);
-    const uint16_t s16 = float_to_f16_bits((hi - lo) / 15.0f);
+    const uint16_t s16 = float_to_f16_bits((hi - lo) / kLevels);
     const uint16_t z16 = float_to_f16_bits(lo);
     const float sc = f16_bits_to_float(s16), z = f16_bits_to_float(z16);
-    uint32_t word = 0;
+    uint32_t q8[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     if (sc > 0.f) {
-      // rint((x - z) / sc) without a division per entry: q0 = rint((x - z) * (1/sc)) is right whenever
-      // the remainder (x - z) - q0 * sc (exact: one fused multiply-add) is clear of half a step; the
-      // rounding of the quotient moves it by < 2^-19 steps, the margin is 2^-18.  The few entries
+      // rint((x - z) / sc) without a division per entry: q0 = rint((x - z) * (1/sc)) is accepted when the
+      // remainder (x - z) - q0 * sc (one fused multiply-add: exact up to 2^-25 of a step) is clear of half
+      // a step by a margin.  Then the true quotient lies within 0.5 - margin of q0, and so does its float32
+      // rounding, which is off by at most |quotient| * 2^-24: below 2^-19 for the quotients up to 16.5
+      // that can still round to a code below the clip (b <= 4), below 2^-15 up to 256.5 (b = 8).  Entries
       // near a tie take the division itself, so every code is the one the definition gives.
       const float inv = 1.0f / sc;
-      const float clear = (0.5f - 0x1.0p-18f) * sc;
+      const float clear = (0.5f - (BITS == 8 ? 0x1.0p-14f : 0x1.0p-18f)) * sc;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float t = x[e] - z;
         float q = rintf(t * inv);
         if (!(fabsf(fmaf(-q, sc, t)) < clear)) q = rintf(t / sc);
-        q = fminf(fmaxf(q, 0.f), 15.f);
-        word |= (uint32_t)q << (4 * e);
+        q8[e] = (uint32_t)fminf(fmaxf(q, 0.f), kLevels);
       }
     }
-    codes[(size_t)row * 16 + c] = word;
+    uint8_t* dst = codes + (size_t)row * (16 * BITS) + c * BITS;
+    if constexpr (BITS == 8) {
+      uint2 w;
+      w.x = q8[0] | (q8[1] << 8) | (q8[2] << 16) | (q8[3] << 24);
+      w.y = q8[4] | (q8[5] << 8) | (q8[6] << 16) | (q8[7] << 24);
+      *reinterpret_cast<uint2*>(dst) = w;
+    } else {
+      uint32_t word = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) word |= q8[e] << (BITS * e);
+      if constexpr (BITS == 4) *reinterpret_cast<uint32_t*>(dst) = word;
+      else *reinterpret_cast<uint16_t*>(dst) = (uint16_t)word;
+    }
     if (c == 0) { vscale[row] = s16; vzero[row] = z16; }
   }
+}
+
+template <typename T>
+void launch_bits(int vbits, unsigned blocks, hipStream_t st, const void* V, uint8_t* codes, uint16_t* vscale,
+                 uint16_t* vzero, long rows) {
+  if (vbits == 2) hipLaunchKernelGGL((value_quant_kernel<T, 2>), dim3(blocks), dim3(256), 0, st, V, codes, vscale, vzero, rows);
+  else if (vbits == 4) hipLaunchKernelGGL((value_quant_kernel<T, 4>), dim3(blocks), dim3(256), 0, st, V, codes, vscale, vzero, rows);
+  else hipLaunchKernelGGL((value_quant_kernel<T, 8>), dim3(blocks), dim3(256), 0, st, V, codes, vscale, vzero, rows);
 }
 
 }  // namespace
 
 int launch_quantize_values(const qjl_shape& sh, int vbits, const void* V, uint8_t* codes,
                            uint16_t* vscale, uint16_t* vzero, hipStream_t st) {
-  if (vbits != 4 || sh.d != 128) return QJL_ERR_UNSUPPORTED;
+  if ((vbits != 2 && vbits != 4 && vbits != 8) || sh.d != 128) return QJL_ERR_UNSUPPORTED;
   const long rows = (long)sh.batch * sh.kv_heads * sh.n;
   long blocks = (rows + 15) / 16;
   const long cap = 32L * device_cu_count();        // grid-stride beyond this
   if (blocks > cap) blocks = cap;
-  uint32_t* cw = reinterpret_cast<uint32_t*>(codes);
   switch (sh.dtype) {
-    case QJL_F32: hipLaunchKernelGGL(value_quant4_kernel<f32_t>, dim3((unsigned)blocks), dim3(256), 0, st, V, cw, vscale, vzero, rows); break;
-    case QJL_F16: hipLaunchKernelGGL(value_quant4_kernel<f16_t>, dim3((unsigned)blocks), dim3(256), 0, st, V, cw, vscale, vzero, rows); break;
-    default: hipLaunchKernelGGL(value_quant4_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, st, V, cw, vscale, vzero, rows); break;
+    case QJL_F32: launch_bits<f32_t>(vbits, (unsigned)blocks, st, V, codes, vscale, vzero, rows); break;
+    case QJL_F16: launch_bits<f16_t>(vbits, (unsigned)blocks, st, V, codes, vscale, vzero, rows); break;
+    default: launch_bits<bf16_t>(vbits, (unsigned)blocks, st, V, codes, vscale, vzero, rows); break;
   }
   return launch_status();
 }

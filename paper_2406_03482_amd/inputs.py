@@ -66,6 +66,9 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("c2v_llama2_7b_decode_4k_v4", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, vbits=4),
     Workload("c3v_long_context_b4_32k_v4", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=4),
     Workload("c5bv_llama3_8b_gqa_b16_8k_v4", 16, 32, 8, 8192, 128, 256, torch.bfloat16, _RS, 1006, 5, vbits=4),
+    # the long-context shape with 2-bit and 8-bit value codes
+    Workload("c3v2_long_context_b4_32k_v2", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=2),
+    Workload("c3v8_long_context_b4_32k_v8", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=8),
     # a whole generation step on the headline shape: append the newest key (Algorithm 1's loop), then attend
     Workload("c2s_llama2_7b_decode_step_4k", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, stream=True),
 ]}

@@ -168,12 +168,12 @@ def test_value_cache_entry_points_validate_on_the_host(L):
     vp = ctypes.c_void_p
     assert L.qjl_quantize_values(ctypes.byref(sh), 4, vp(None), ok, ok, ok, None) == INVALID
     assert L.qjl_quantize_values(ctypes.byref(sh), 0, ok, ok, ok, ok, None) == INVALID
-    assert L.qjl_quantize_values(ctypes.byref(sh), 2, ok, ok, ok, ok, None) == UNSUPPORTED      # only 4-bit codes are built
+    assert L.qjl_quantize_values(ctypes.byref(sh), 3, ok, ok, ok, ok, None) == UNSUPPORTED      # codes of 2, 4 or 8 bits
     d64 = QJLShape(1, 4, 2, 100, 64, 256, 2, 1.0)
     assert L.qjl_quantize_values(ctypes.byref(d64), 4, ok, ok, ok, ok, None) == UNSUPPORTED
     args = (ok, ok, ok, ok, ok, ok, ok, ok)
     assert L.qjl_decode_attention_vq(ctypes.byref(sh), 4, *args, vp(None), ctypes.c_size_t(0), None, None, None) == WORKSPACE
-    assert L.qjl_decode_attention_vq(ctypes.byref(sh), 2, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
+    assert L.qjl_decode_attention_vq(ctypes.byref(sh), 3, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
     f32 = QJLShape(1, 4, 2, 100, 128, 256, 0, 1.0)
     assert L.qjl_decode_attention_vq(ctypes.byref(f32), 4, *args, ok, ctypes.c_size_t(1 << 30), None, None, None) == UNSUPPORTED
     assert L.qjl_decode_attention_vq(ctypes.byref(sh), 4, ok, ok, ok, ok, vp(None), ok, ok, ok, ok,

@@ -31,24 +31,25 @@ def _need_gpu_and_lib():
     qjl.lib()
 
 
+@pytest.mark.parametrize("vbits", [4, 2, 8])
 @pytest.mark.parametrize("dt,B,Hkv,n", [("bf16", 2, 3, 333), ("f16", 1, 2, 1000), ("f32", 1, 1, 257),
                                         ("bf16", 1, 1, 1), ("bf16", 1, 32, 4096)])
-def test_quantize_values_is_bit_exact(dt, B, Hkv, n):
-    say(f"[values] dt={dt} B={B} Hkv={Hkv} n={n}")
+def test_quantize_values_is_bit_exact(dt, B, Hkv, n, vbits):
+    say(f"[values] dt={dt} B={B} Hkv={Hkv} n={n} vbits={vbits}")
     V = inputs.make_normal((B, Hkv, n, 128), DT[dt], 900 + n, DEV)
     V[0, 0, 0] = 0.75                                          # a constant row: scale 0
     if n > 2:
         V[0, 0, 1] *= 37.0                                     # a wide row
         V[0, 0, 2, 5:] = V[0, 0, 2, 4]                         # two distinct values only
-    codes, sc, z = qjl.qjl_quantize_values(V, 4)
+    codes, sc, z = qjl.qjl_quantize_values(V, vbits)
     torch.cuda.synchronize()
-    rc, rs, rz = orc.quantize_values(inputs.to_f64(V), 4)
+    rc, rs, rz = orc.quantize_values(inputs.to_f64(V), vbits)
     assert np.array_equal(sc.cpu().numpy().view(np.uint16), rs.view(np.uint16))
     assert np.array_equal(z.cpu().numpy().view(np.uint16), rz.view(np.uint16))
     diff = int((codes.cpu().numpy() != rc).sum())
     say(f"  code bytes differing: {diff} of {rc.size}")
     assert diff == 0
-    c2, s2, z2 = qjl.qjl_quantize_values(V, 4)
+    c2, s2, z2 = qjl.qjl_quantize_values(V, vbits)
     assert torch.equal(codes, c2) and torch.equal(sc, s2) and torch.equal(z, z2)
 
 
@@ -66,9 +67,10 @@ VQ_CASES = [
 ]
 
 
+@pytest.mark.parametrize("vbits", [4, 2, 8])
 @pytest.mark.parametrize("dt,B,Hq,Hkv,n,m,scale", VQ_CASES)
-def test_decode_attention_vq_parity(dt, B, Hq, Hkv, n, m, scale):
-    say(f"[decode vq] dt={dt} B={B} Hq={Hq} Hkv={Hkv} n={n} m={m} scale={scale}")
+def test_decode_attention_vq_parity(dt, B, Hq, Hkv, n, m, scale, vbits):
+    say(f"[decode vq] dt={dt} B={B} Hq={Hq} Hkv={Hkv} n={n} m={m} scale={scale} vbits={vbits}")
     d = 128
     K = inputs.make_keys(B, Hkv, n, d, DT[dt], 700 + n, DEV, outliers=4)
     Q = inputs.make_normal((B, Hq, d), DT[dt], 71, DEV)
@@ -76,36 +78,37 @@ def test_decode_attention_vq_parity(dt, B, Hq, Hkv, n, m, scale):
     S = qjl.qjl_make_sketch(10, m, d, DT[dt], DEV)
     S64 = inputs.to_f64(S)
     bits, nu16, _ = orc.quantize_keys(inputs.to_f64(K), S64)            # the oracle's caches
-    vc, vs, vz = orc.quantize_values(inputs.to_f64(V), 4)
-    ref = orc.decode_attention_vq(inputs.to_f64(Q), S64, bits, nu16, vc, vs, vz, 4, scale)
+    vc, vs, vz = orc.quantize_values(inputs.to_f64(V), vbits)
+    ref = orc.decode_attention_vq(inputs.to_f64(Q), S64, bits, nu16, vc, vs, vz, vbits, scale)
     up = lambda a: torch.from_numpy(a).to(DEV)
-    args = (Q, S, up(bits), up(nu16), up(vc), up(vs), up(vz), 4, scale)
+    args = (Q, S, up(bits), up(nu16), up(vc), up(vs), up(vz), vbits, scale)
     out = qjl.qjl_decode_attention_vq(*args)
     err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref)))
     say(f"  max abs error {err:.3g}")
     assert err <= 2e-3
     assert torch.equal(out, qjl.qjl_decode_attention_vq(*args))
     if n == 1:
-        assert np.allclose(out.cpu().numpy()[0, 0], orc.dequantize_values(vc, vs, vz, 4)[0, 0, 0], atol=2e-3)
+        assert np.allclose(out.cpu().numpy()[0, 0], orc.dequantize_values(vc, vs, vz, vbits)[0, 0, 0], atol=2e-3)
 
 
-def test_vq_pipeline_on_the_gpu_and_distance_to_unquantized_values():
+@pytest.mark.parametrize("vbits,max_shift", [(4, 0.1), (2, 0.4), (8, 0.01)])
+def test_vq_pipeline_on_the_gpu_and_distance_to_unquantized_values(vbits, max_shift):
     B, Hq, Hkv, n, d, m, scale = 1, 8, 8, 2048, 128, 256, 0.0884
     K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 81, DEV, outliers=4)
     Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 82, DEV)
     V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 83, DEV)
     S = qjl.qjl_make_sketch(11, m, d, torch.bfloat16, DEV)
     bits, norms = qjl.qjl_quantize_keys(K, S)
-    vc, vs, vz = qjl.qjl_quantize_values(V, 4)
-    out = qjl.qjl_decode_attention_vq(Q, S, bits, norms, vc, vs, vz, 4, scale).cpu().numpy().astype(np.float64)
+    vc, vs, vz = qjl.qjl_quantize_values(V, vbits)
+    out = qjl.qjl_decode_attention_vq(Q, S, bits, norms, vc, vs, vz, vbits, scale).cpu().numpy().astype(np.float64)
     full = qjl.qjl_decode_attention(Q, S, bits, norms, V, scale).cpu().numpy().astype(np.float64)
     ref = orc.decode_attention_vq(inputs.to_f64(Q), inputs.to_f64(S), bits.cpu().numpy(), norms.cpu().numpy(),
-                                  *[t.cpu().numpy() for t in (vc, vs, vz)], 4, scale)
+                                  *[t.cpu().numpy() for t in (vc, vs, vz)], vbits, scale)
     assert float(np.max(np.abs(out - ref))) <= 2e-3
-    # 4-bit values: the output moves by a fraction of a quantization step (N(0,1) rows: step ~ 0.5)
+    # the output moves by a fraction of a quantization step (N(0,1) rows: step ~ 5 / (2^b - 1))
     shift = float(np.sqrt(np.mean((out - full) ** 2)))
-    say(f"[vq chain] rms distance to attention on bf16 values: {shift:.4f}")
-    assert shift < 0.1
+    say(f"[vq chain] {vbits}-bit values: rms distance to attention on bf16 values: {shift:.4f}")
+    assert shift < max_shift
 
 
 @pytest.mark.parametrize("name,units", [("c2_llama2_7b_decode_4k", 8), ("c3_long_context_b4_32k", 3)])
@@ -142,7 +145,8 @@ def test_full_size_vq_sampled(name, units):
     assert worst <= 2e-3 and np.all(np.isfinite(out))
 
 
-def test_quantize_values_on_rows_full_of_ties():
+@pytest.mark.parametrize("vbits", [4, 2, 8])
+def test_quantize_values_on_rows_full_of_ties(vbits):
     """Rows whose entries sit exactly on, or one bf16 step away from, the midpoints between codes: the kernel's
     division-free shortcut must hand every such entry to the exact path."""
     V = torch.zeros((1, 4, 4096, 128), dtype=torch.bfloat16, device=DEV)
@@ -151,8 +155,17 @@ def test_quantize_values_on_rows_full_of_ties():
     V[0, 1] = (torch.randint(0, 61, (4096, 128), device=DEV, generator=g).float() * 0.125).to(torch.bfloat16)
     V[0, 2] = (torch.randn((4096, 128), device=DEV, generator=g) * 3).to(torch.bfloat16)
     V[0, 3] = (torch.randint(-40, 41, (4096, 128), device=DEV, generator=g).float() * 0.0625).to(torch.bfloat16)
-    codes, sc, z = qjl.qjl_quantize_values(V, 4)
-    rc, rs, rz = orc.quantize_values(inputs.to_f64(V), 4)
+    if vbits == 8:                                   # steps of 1/4 over a range of 255/2: entries on every midpoint
+        V[0, 0] = (torch.arange(128, device=DEV).float() * 0.25).to(torch.bfloat16)
+        V[0, 0, :, 127] = 127.5
+        V[0, 1] = (torch.randint(0, 511, (4096, 128), device=DEV, generator=g).float() * 0.25).to(torch.bfloat16)
+        V[0, 1, :, 0] = 0.0
+        V[0, 1, :, 1] = 127.5
+    if vbits == 2:                                   # steps of 1/2 over a range of 3: every second entry is a tie
+        V[0, 0] = (torch.arange(128, device=DEV).float() % 7 * 0.5).to(torch.bfloat16)
+        V[0, 1] = (torch.randint(0, 13, (4096, 128), device=DEV, generator=g).float() * 0.25).to(torch.bfloat16)
+    codes, sc, z = qjl.qjl_quantize_values(V, vbits)
+    rc, rs, rz = orc.quantize_values(inputs.to_f64(V), vbits)
     assert np.array_equal(sc.cpu().numpy().view(np.uint16), rs.view(np.uint16))
     assert np.array_equal(z.cpu().numpy().view(np.uint16), rz.view(np.uint16))
     assert int((codes.cpu().numpy() != rc).sum()) == 0
