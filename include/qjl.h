@@ -277,7 +277,10 @@ int qjl_append_keys(const qjl_shape* shape, int pos, int count, const void* K_ne
  * caches, then out[B,Hq,d] <- attention of Q[B,Hq,d] over rows 0..pos
  * (Algorithm 1 EstimateScores + Eq. (1)).  Row `pos` of V[B,Hkv,n,d] must
  * already hold the new token's value.  Workspace:
- * qjl_decode_workspace_bytes(shape) covers every pos.
+ * qjl_decode_workspace_bytes(shape) covers every pos.  For 16-bit types the
+ * key is quantized inside the attention kernel (one launch less than
+ * qjl_append_keys + qjl_decode_attention); the cache row is written by that
+ * kernel and is complete when the call's work on `stream` is.
  */
 int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const void* Q, const void* S,
                     uint8_t* bits, uint16_t* norms, const void* V, float* out, void* workspace,

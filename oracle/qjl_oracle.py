@@ -54,7 +54,7 @@ Readings of points the paper leaves open (all restated where they are used):
     the standard asymmetric token-wise scheme: per (batch, kv head, token)
     zero point = the row's minimum, scale = (max - min)/(2^b - 1), both stored
     in binary16; code = round-to-nearest-even of (v - min)/scale clipped to
-    [0, 2^b - 1], taken against the *stored* zero point and scale; b = 4 or 2;
+    [0, 2^b - 1], taken against the *stored* zero point and scale; b = 2, 4 or 8;
     element t of a row occupies bits [b*t, b*t + b) of the row's bytes, LSB
     first; a value is read back as min + code * scale.  The code is an integer
     decided by floating point, so it is computed in float32 with exactly the

@@ -238,6 +238,9 @@ int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const vo
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (shape->dtype != QJL_F32)                     // 16-bit types: the attention kernel quantizes the new key itself
+    return launch_decode(now, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, shape->n, out, workspace,
+                         st, nullptr, nullptr, K_new, bits, norms);
   rc = launch_append_keys(*shape, K_new, 1, pos, S, bits, norms, st);
   if (rc != QJL_OK) return rc;
   return launch_decode(now, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, shape->n, out, workspace, st,

@@ -166,7 +166,11 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
                   const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
-                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after);
+                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after, const void* K_new = nullptr,
+                  uint8_t* bits_w = nullptr, uint16_t* norms_w = nullptr);
+// K_new != nullptr (16-bit types, m_out = 0, no value codes): K_new[B,Hkv,1,d] is the key of position sh.n - 1;
+// it is quantized inside the attention kernel, attended to, and written to row sh.n - 1 of bits_w / norms_w
+// (the same arrays as bits / norms).
 // n_cap: rows per (batch, kv head) in bits / norms / V (0: exactly sh.n, the number of keys attended to).
 int launch_append_keys(const qjl_shape& sh, const void* K_new, int t, int pos, const void* S, uint8_t* bits,
                        uint16_t* norms, hipStream_t st);

@@ -42,7 +42,7 @@ struct decode_args {
   const uint16_t* norms;  // [B,Hkv,n]
   const uint16_t* norms2; // [B,Hkv,n] norm of the outlier part (two-part codes only)
   size_t s_head_stride;   // elements between the sketches of consecutive (batch, kv head) pairs
-  const void* V;          // [B,Hkv,n,128], or the 4-bit codes [B,Hkv,n,64 bytes] of quantized values
+  const void* V;          // [B,Hkv,n,128], or the codes [B,Hkv,n,16*b bytes] of values quantized to b bits
   const uint16_t* vscale; // [B,Hkv,n] binary16 scale and zero point of a token's values (quantized values only)
   const uint16_t* vzero;
   float* part;            // [B,Hq,nsplit,132]
@@ -52,6 +52,10 @@ struct decode_args {
   int nsplit, chunk;
   float coef2;            // scale * sqrt(pi/2) / m * log2(e); m = bits of the (first) code part
   float coef2b;           // the same for the second part
+  // Streaming (Algorithm 1 as a loop): the key of position n - 1 arrives with the call.
+  const void* Knew;       // [B,Hkv,1,128], or null
+  uint32_t* bits_w;       // the caches again, writable: row n - 1 is written by this call
+  uint16_t* norms_w;
 };
 
 // 16 bytes of V -> 8 floats (16-bit types) ...
@@ -193,7 +197,7 @@ template <> struct vtile_q<8> {
 // per token (Section 3.2).  o = sum_j p_j (zero_j + scale_j c_j): the weight
 // that goes to the value pass is p_j scale_j, and sum_j p_j zero_j, the same for
 // every channel, is carried next to the softmax denominator.
-template <typename T, int GT, int MW, int MWB, int VB>
+template <typename T, int GT, int MW, int MWB, int VB, bool AP>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes) * 64,
                                   T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
@@ -208,6 +212,10 @@ decode_kernel(decode_args a) {
   // the 4-bit tables are dead once the byte tables exist; their space then
   // holds the per-wave probability buffers.  The wave-merge records reuse the
   // byte tables after the last key has been scored.
+  // AP: the projections of the new key (M floats), its squared norm, then its
+  // code words and its norm as stored -- behind everything else
+  float* sk = lut + 32 * M * GT;
+  uint32_t* newcode = reinterpret_cast<uint32_t*>(sk + M + 1);
   float* pbuf_all = nib;                              // [kNW][64*GT]
   float* merge = lut;                                 // [kNW][GT][132]
   static_assert(kNW * 64 <= 4 * M, "probability buffers must fit the 4-bit tables");
@@ -240,10 +248,17 @@ decode_kernel(decode_args a) {
   constexpr int kPasses = M / kRowsPerPass;
   static_assert(M % kRowsPerPass == 0, "whole passes over S");
   slice8<T> qs[GT], srow[kPasses];
+  slice8<T> ks;                                       // AP: this lane's slice of the new key
+  // AP: the new key is row n - 1; the workgroups whose chunk holds that row
+  // quantize it themselves (same S, same walk as for the queries), use its code
+  // from LDS and, the first group of query heads only, write it to the caches.
+  const int pos = a.n - 1;
+  const bool has_new = AP && pos >= k_begin && pos < k_end;   // uniform
   {
     const int c16 = tid & 15, r16 = tid >> 4;
 #pragma unroll
     for (int g = 0; g < GT; ++g) qs[g].load(a.Q, (hq0 + g) * kD + c16 * 8);
+    if constexpr (AP) ks.load(a.Knew, (size_t)bk * kD + c16 * 8);
     const size_t s0 = (size_t)bk * a.s_head_stride;
 #pragma unroll
     for (int u = 0; u < kPasses; ++u) srow[u].load(a.S, s0 + (size_t)(u * kRowsPerPass + r16) * kD + c16 * 8);
@@ -307,9 +322,31 @@ decode_kernel(decode_args a) {
         const float t = row16_sum(dot8(srow[u], qs[g]));
         if (c16 == 0) sq[g * M + u * kRowsPerPass + r16] = t;
       }
+      if constexpr (AP) {                             // every workgroup: no branch inside this stretch of code
+        const float t = row16_sum(dot8(srow[u], ks));
+        if (c16 == 0) sk[u * kRowsPerPass + r16] = t;
+      }
+    }
+    if constexpr (AP) {
+      const float kk = row16_sum(dot8(ks, ks));
+      if (tid == 0) sk[M] = kk;
     }
   }
   __syncthreads();
+  if constexpr (AP) {
+    if (has_new) {                                    // bit i of the code = [(S k)_i >= 0]: one ballot per 64 projections
+#pragma unroll
+      for (int i0 = 0; i0 < M; i0 += kNW * 64) {
+        const int i = i0 + tid;                       // more threads than projections for small m
+        const uint64_t bal = __ballot(i < M && sk[min(i, M - 1)] >= 0.f);
+        if ((lane & 31) == 0 && i < M) {
+          const uint32_t word = (uint32_t)(bal >> (lane & 32));
+          newcode[i >> 5] = word;
+        }
+      }
+      if (tid == 0) newcode[MW] = float_to_f16_bits(sqrtf(sk[M]));
+    }
+  }
   build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -333,6 +370,15 @@ decode_kernel(decode_args a) {
   for (; k0 < k_end; k0 += kNW * 64) {
     const int kn = k0 + kNW * 64;
     const bool have_next = kn < k_end;
+    if constexpr (AP) {                               // the lane of the new key takes its code from LDS
+      if (has_new && pos >= k0 && pos < k0 + 64) {    // uniform
+        if (k0 + lane == pos) {
+#pragma unroll
+          for (int w = 0; w < MW; ++w) wcur[w] = newcode[w];
+          ncur = (uint16_t)newcode[MW];
+        }
+      }
+    }
     // ---- scores of this block: lane <-> key
     const PV s = key_inner<GT, MW, 0, MWA>(wcur, lut);
     PV s2 = 0.f;
@@ -453,6 +499,12 @@ decode_kernel(decode_args a) {
       if (ch == 0) { rec[0] = mx; rec[1] = L; rec[2] = Z; }
     }
   }
+  if constexpr (AP) {                                   // the new key's row of the caches, last: no store ahead of the loop's loads
+    if (has_new && blockIdx.y == 0) {
+      if (tid < MW) a.bits_w[(row0 + pos) * MW + tid] = newcode[tid];
+      if (tid == 0) a.norms_w[row0 + pos] = (uint16_t)newcode[MW];
+    }
+  }
 }
 
 // Merge the per-chunk records of one query head: out = sum_s o_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
@@ -506,14 +558,14 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
   if (half == 0) out[head * kD + ch] = (O + s_o[ch] + Zc + s_zsum) / (L + s_lsum);
 }
 
-template <typename T, int GT, int MW, int MWB, int VB>
+template <typename T, int GT, int MW, int MWB, int VB, bool AP>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   static bool attr_set = false;
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes);
-  const size_t lds = decode_lds_bytes(GT, MW * 32);
+  const size_t lds = decode_lds_bytes(GT, MW * 32) + (AP ? (MW * 32 + MW + 8) * sizeof(float) : 0);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_status(e);
     attr_set = true;
@@ -522,20 +574,20 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
   if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
   if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
-    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP>), grid, dim3(kNW * 64), (uint32_t)lds, st,
                           ev0, ev1, 0u, a);
   else
-    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB>), grid, dim3(kNW * 64), lds, st, a);
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP>), grid, dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
-template <typename T, int MW, int MWB, int VB = 0>
+template <typename T, int MW, int MWB, int VB = 0, bool AP = false>
 int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   switch (plan.gt) {
-    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VB>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
-    default: return launch_t<T, 1, MW, MWB, VB>(sh, plan, a, st, ev0, ev1);
+    case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VB, AP>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VB, AP>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+    default: return launch_t<T, 1, MW, MWB, VB, AP>(sh, plan, a, st, ev0, ev1);
   }
 }
 
@@ -556,6 +608,19 @@ int launch_m(const qjl_shape& sh, int m_out, int vbits, const decode_plan& plan,
         case 512 * 16 + 2: return launch_g<T, 16, 0, 2>(sh, plan, a, st, ev0, ev1);
         case 512 * 16 + 4: return launch_g<T, 16, 0, 4>(sh, plan, a, st, ev0, ev1);
         case 512 * 16 + 8: return launch_g<T, 16, 0, 8>(sh, plan, a, st, ev0, ev1);
+        default: return QJL_ERR_UNSUPPORTED;
+      }
+    } else {
+      return QJL_ERR_UNSUPPORTED;
+    }
+  }
+  if (a.Knew != nullptr) {                          // streaming: 16-bit types, one-part codes, unquantized values
+    if constexpr (T::bytes == 2) {
+      if (m_out != 0) return QJL_ERR_UNSUPPORTED;
+      switch (sh.m) {
+        case 128: return launch_g<T, 4, 0, 0, true>(sh, plan, a, st, ev0, ev1);
+        case 256: return launch_g<T, 8, 0, 0, true>(sh, plan, a, st, ev0, ev1);
+        case 512: return launch_g<T, 16, 0, 0, true>(sh, plan, a, st, ev0, ev1);
         default: return QJL_ERR_UNSUPPORTED;
       }
     } else {
@@ -638,13 +703,15 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
                   const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
-                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after) {
+                  hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after, const void* K_new, uint8_t* bits_w,
+                  uint16_t* norms_w) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
   decode_args a;
   a.Q = Q; a.S = S; a.bits = bits; a.norms = norms; a.V = V;
   a.norms2 = norms_out;
   a.vscale = vscale; a.vzero = vzero;
+  a.Knew = K_new; a.bits_w = reinterpret_cast<uint32_t*>(bits_w); a.norms_w = norms_w;
   a.s_head_stride = m_out > 0 ? (size_t)(sh.m + m_out) * kD : 0;
   a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);

@@ -514,26 +514,36 @@ def test_append_keys_parity(dt, B, Hkv, t, m, pos):
     assert bad2 == 0
 
 
-def test_decode_steps_stream_into_a_cache():
-    """Eight generation steps from a prefilled cache: after every step the cache rows and the attention output
+@pytest.mark.parametrize("dt,B,Hq,Hkv,cap,m,n0", [
+    ("bf16", 1, 8, 4, 300, 256, 292),        # two query heads per kv head
+    ("f16", 1, 4, 1, 132, 512, 125),         # four query heads per kv head, steps across a 128-key boundary
+    ("bf16", 2, 2, 2, 68, 128, 61),          # fewer projections than threads, steps across a 64-key boundary
+    ("bf16", 1, 3, 1, 5, 256, 0),            # from an empty cache
+    ("f32", 1, 2, 1, 40, 256, 36),           # fp32: the key is appended by a kernel of its own
+])
+def test_decode_steps_stream_into_a_cache(dt, B, Hq, Hkv, cap, m, n0):
+    """Generation steps from a prefilled cache: after every step the cache rows and the attention output
     match the oracle's stream, which in turn equals quantizing everything at once."""
-    B, Hq, Hkv, cap, d, m, scale, n0 = 1, 8, 4, 300, 128, 256, 0.0884, 292
-    K = inputs.make_keys(B, Hkv, cap, d, torch.bfloat16, 301, DEV, outliers=4)
-    V = inputs.make_normal((B, Hkv, cap, d), torch.bfloat16, 302, DEV)
-    Qs = inputs.make_normal((cap, B * Hq, d), torch.bfloat16, 303, DEV).view(cap, B, Hq, d)
-    S = qjl.qjl_make_sketch(6, m, d, torch.bfloat16, DEV)
+    d, scale = 128, 0.0884
+    say(f"[stream] dt={dt} B={B} Hq={Hq} Hkv={Hkv} cap={cap} m={m} from {n0}")
+    K = inputs.make_keys(B, Hkv, cap, d, DT[dt], 301, DEV, outliers=4)
+    V = inputs.make_normal((B, Hkv, cap, d), DT[dt], 302, DEV)
+    Qs = inputs.make_normal((cap, B * Hq, d), DT[dt], 303, DEV).view(cap, B, Hq, d)
+    S = qjl.qjl_make_sketch(6, m, d, DT[dt], DEV)
     K64, V64, S64 = inputs.to_f64(K), inputs.to_f64(V), inputs.to_f64(S)
-    rb, rn, _ = orc.quantize_keys(K64[:, :, :n0], S64)                       # the oracle's prefill
     ob = np.zeros((B, Hkv, cap, m // 8), dtype=np.uint8); on = np.zeros((B, Hkv, cap), dtype=np.float16)
-    ob[:, :, :n0] = rb; on[:, :, :n0] = rn
+    if n0 > 0:
+        rb, rn, _ = orc.quantize_keys(K64[:, :, :n0], S64)                   # the oracle's prefill
+        ob[:, :, :n0] = rb; on[:, :, :n0] = rn
     bits = torch.from_numpy(ob.copy()).to(DEV); norms = torch.from_numpy(on.copy()).to(DEV)
-    ws = torch.empty((qjl.qjl_decode_workspace_bytes(B, Hq, Hkv, cap, d, m, torch.bfloat16),), dtype=torch.uint8, device=DEV)
+    ws = torch.empty((qjl.qjl_decode_workspace_bytes(B, Hq, Hkv, cap, d, m, DT[dt]),), dtype=torch.uint8, device=DEV)
     worst = 0.0
     for pos in range(n0, cap):
         out = qjl.qjl_decode_step(Qs[pos].contiguous(), K[:, :, pos:pos + 1].contiguous(), S, bits, norms, V, pos, scale, workspace=ws)
         ref = orc.decode_step(inputs.to_f64(Qs[pos]), S64, ob, on, V64, K64[:, :, pos:pos + 1], pos, scale)
         bad, _, _ = bits_report(bits[:, :, pos:pos + 1].cpu().numpy(), K64[:, :, pos:pos + 1], S64)
         assert bad == 0
+        assert_norms(norms[:, :, pos:pos + 1].cpu().numpy(), K64[:, :, pos:pos + 1])
         bits[:, :, pos] = torch.from_numpy(ob[:, :, pos]).to(DEV)          # keep both sides on the oracle's code
         norms[:, :, pos] = torch.from_numpy(on[:, :, pos]).to(DEV)
         worst = max(worst, assert_attention(out.cpu().numpy(), ref))
