@@ -244,24 +244,39 @@ decode_kernel(decode_args a) {
 
   // ---- the rows of S and the queries first: loads come back in issue order, and
   // S q (then the tables) is the first thing that has to be ready
-  constexpr int kRowsPerPass = kNW * 4;                // 16 lanes per row
+  // LPR lanes share a row of S.  With 16 every lane holds one 8-element slice per
+  // row and a row's sum takes four DPP steps; with 4 a lane holds four slices
+  // (slices c, c+4, c+8, c+12, so that a quad still reads 64 contiguous bytes)
+  // and two steps finish four times as many rows at once.  The second form
+  // needs four query slices per head in registers: used while GT <= 2.
+  constexpr int LPR = GT <= 2 ? 4 : 16;
+  constexpr int SPL = 16 / LPR;                        // slices per lane and row
+  constexpr int kRowsPerPass = kNW * 64 / LPR;
   constexpr int kPasses = M / kRowsPerPass;
   static_assert(M % kRowsPerPass == 0, "whole passes over S");
-  slice8<T> qs[GT], srow[kPasses];
-  slice8<T> ks;                                       // AP: this lane's slice of the new key
+  slice8<T> qs[GT][SPL], srow[kPasses][SPL];
+  slice8<T> ks[SPL];                                  // AP: this lane's slices of the new key
   // AP: the new key is row n - 1; the workgroups whose chunk holds that row
   // quantize it themselves (same S, same walk as for the queries), use its code
   // from LDS and, the first group of query heads only, write it to the caches.
   const int pos = a.n - 1;
   const bool has_new = AP && pos >= k_begin && pos < k_end;   // uniform
   {
-    const int c16 = tid & 15, r16 = tid >> 4;
+    const int c16 = tid & (LPR - 1), r16 = tid / LPR;
 #pragma unroll
-    for (int g = 0; g < GT; ++g) qs[g].load(a.Q, (hq0 + g) * kD + c16 * 8);
-    if constexpr (AP) ks.load(a.Knew, (size_t)bk * kD + c16 * 8);
+    for (int g = 0; g < GT; ++g)
+#pragma unroll
+      for (int i = 0; i < SPL; ++i) qs[g][i].load(a.Q, (hq0 + g) * kD + (c16 + LPR * i) * 8);
+    if constexpr (AP) {
+#pragma unroll
+      for (int i = 0; i < SPL; ++i) ks[i].load(a.Knew, (size_t)bk * kD + (c16 + LPR * i) * 8);
+    }
     const size_t s0 = (size_t)bk * a.s_head_stride;
 #pragma unroll
-    for (int u = 0; u < kPasses; ++u) srow[u].load(a.S, s0 + (size_t)(u * kRowsPerPass + r16) * kD + c16 * 8);
+    for (int u = 0; u < kPasses; ++u)
+#pragma unroll
+      for (int i = 0; i < SPL; ++i)
+        srow[u][i].load(a.S, s0 + (size_t)(u * kRowsPerPass + r16) * kD + (c16 + LPR * i) * 8);
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- then the first block of this wave: its HBM reads are in flight while
@@ -314,21 +329,30 @@ decode_kernel(decode_args a) {
 
   __builtin_amdgcn_sched_barrier(0);
   {
-    const int c16 = tid & 15, r16 = tid >> 4;
+    const int c16 = tid & (LPR - 1), r16 = tid / LPR;
+    auto row_dot = [&](const slice8<T> (&x)[SPL], const slice8<T> (&y)[SPL]) {   // sum over the row's LPR lanes
+      float t = dot8(x[0], y[0]);
+#pragma unroll
+      for (int i = 1; i < SPL; ++i) t += dot8(x[i], y[i]);
+      if constexpr (LPR == 16) return row16_sum(t);
+      t += QJL_DPP_F(t, 0xB1);   // quad_perm [1,0,3,2]
+      t += QJL_DPP_F(t, 0x4E);   // quad_perm [2,3,0,1]
+      return t;
+    };
 #pragma unroll
     for (int u = 0; u < kPasses; ++u) {
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
-        const float t = row16_sum(dot8(srow[u], qs[g]));
+        const float t = row_dot(srow[u], qs[g]);
         if (c16 == 0) sq[g * M + u * kRowsPerPass + r16] = t;
       }
       if constexpr (AP) {                             // every workgroup: no branch inside this stretch of code
-        const float t = row16_sum(dot8(srow[u], ks));
+        const float t = row_dot(srow[u], ks);
         if (c16 == 0) sk[u * kRowsPerPass + r16] = t;
       }
     }
     if constexpr (AP) {
-      const float kk = row16_sum(dot8(ks, ks));
+      const float kk = row_dot(ks, ks);
       if (tid == 0) sk[M] = kk;
     }
   }
