@@ -697,10 +697,19 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
   else if (G % 2 == 0 && mt * 2 <= 1024) gt = 2;
   const long units = (long)sh.batch * sh.kv_heads * (G / gt);
   const size_t lds = decode_lds_bytes(gt, mt);
-  long occ = (160 * 1024) / (long)lds;              // workgroups per CU by LDS
-  if (occ < 1) occ = 1;
-  if (occ > 4) occ = 4;
-  const long slots = (long)device_cu_count() * occ;
+  const long occ = (160 * 1024) / (long)lds;        // workgroups a CU can hold, by LDS
+  // One workgroup per CU: what a workgroup does before its first key (its
+  // share of S through L2, S q, the tables: about 3 us) is paid once per
+  // workgroup, and with more workgroups per CU it is paid more often for
+  // shorter chunks (32 units of 4096 keys: 10.1 us with 8 chunks each, 11.1
+  // with 16, 14.5 with 32; of 16384 keys: 27 / 30 / 33 us).  Two per CU where
+  // each still gets a long stream (>= 4096 keys): there a second workgroup hides
+  // latency that the first cannot (long contexts with 4-bit values: 89 us
+  // against 109).
+  const long cus = device_cu_count();
+  long per_cu = 1;
+  if (occ >= 2 && (long)sh.n / ((2 * cus + units - 1) / units) >= 4096) per_cu = 2;
+  const long slots = cus * per_cu;
   long nsplit = (slots + units - 1) / units;
   const long min_chunk = 64L * decode_waves(gt, mt, sh.dtype == QJL_F32 ? 4 : 2);  // one 64-key block per wave
   long max_split = ((long)sh.n + min_chunk - 1) / min_chunk;
