@@ -45,11 +45,11 @@ value_quant_kernel(const void* __restrict__ V, uint8_t* __restrict__ codes,
       const float inv = 1.0f / sc;
       const float clear = (0.5f - (BITS == 8 ? 0x1.0p-14f : 0x1.0p-18f)) * sc;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float t = x[e] - z;
-        float q = rintf(t * inv);
+      for (int e = 0; e < 8; ++e) {                  // a branch per entry: exact ties are common enough with
+        const float t = x[e] - z;                    // 8- to 11-bit inputs that one branch for all eight
+        float q = rintf(t * inv);                    // would send most waves through eight divisions
         if (!(fabsf(fmaf(-q, sc, t)) < clear)) q = rintf(t / sc);
-        q8[e] = (uint32_t)fminf(fmaxf(q, 0.f), kLevels);
+        q8[e] = (uint32_t)__builtin_amdgcn_fmed3f(q, 0.f, kLevels);
       }
     }
     uint8_t* dst = codes + (size_t)row * (16 * BITS) + c * BITS;
