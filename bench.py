@@ -246,6 +246,47 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     }
 
 
+def bench_scores(qjl, inputs, ev, w, dev, steps, warmup):
+    """The estimator on its own (Eq. (4) for every cached key): S q, then one fp32 score per key and query head
+    written to HBM.  34 bytes read per key and kv head, 4 written per key and query head."""
+    import torch
+    K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, dev, w.outliers)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    bits, norms = qjl.qjl_quantize_keys(K, S)
+    del K
+    Q = inputs.make_normal((w.batch, w.q_heads, w.d), w.dtype, w.data_seed + 7919, dev)
+    sq = torch.empty((w.batch, w.q_heads, w.m), dtype=torch.float32, device=dev)
+    out = torch.empty((w.batch, w.q_heads, w.n), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        qjl.qjl_project_query(Q, S, sq)
+        qjl.qjl_scores(sq, bits, norms, w.scale, out=out)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    a, b = ev.create(), ev.create()
+    ev.record(a, stream)
+    for _ in range(steps):
+        step()
+    ev.record(b, stream)
+    ms = ev.elapsed_ms(a, b) / steps
+    ev.destroy(a)
+    ev.destroy(b)
+    algo_bytes = w.batch * w.n * (w.kv_heads * (w.m // 8 + 2) + w.q_heads * 4)
+    achieved = algo_bytes / (ms * 1e-3) / 1e9
+    return {
+        "workload": w.name + "_scores_only",
+        "metric": "estimated scores keys/s/GPU",
+        "value": w.key_heads / (ms * 1e-3),
+        "ms_per_step": ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "project128_kernel + scores_kernel",
+                     "kernel_ms": ms, "algorithmic_bytes": algo_bytes},
+    }
+
+
 def bench_value_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     """Token-wise 4-bit quantization of a value cache of the prefill workload's shape (HBM-bound)."""
     import torch
@@ -414,6 +455,7 @@ def main() -> int:
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 50, 5))
         extra.append(bench_value_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
+        extra.append(bench_scores(qjl, inputs, ev, inputs.WORKLOADS["c3_long_context_b4_32k"], dev, 100, 10))
         line["setup_kernels"] = bench_sketches(qjl, ev, dev)
         line["other_workloads"] = extra
 
