@@ -335,6 +335,45 @@ def test_full_size_decode_sampled(name, units):
     say(f"  worst attention error over {len(refs) * G} heads: {worst:.3g}")
 
 
+def test_full_size_decode_step_sampled():
+    """The streaming workload as bench.py runs it: the newest key goes into the last row of a full cache and is
+    attended to in the same launch.  Sampled (batch, kv head) units against the oracle's stream."""
+    w = inputs.WORKLOADS["c2s_llama2_7b_decode_step_4k"]
+    say(f"[full decode step] {w.name}")
+    K, Q, V = inputs.make_workload_tensors(w, DEV)
+    S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, DEV)
+    S64, Q64 = inputs.to_f64(S), inputs.to_f64(Q)
+    pos = w.n - 1
+    bits_d, nu_d = qjl.qjl_quantize_keys(K, S)
+    bits_d[:, :, pos] = 0                                               # the row the step has to write
+    nu_d[:, :, pos] = 0
+    G = w.q_heads // w.kv_heads
+    picked = _sample_units(w.batch, w.kv_heads, 6, w.data_seed)
+    refs = {}
+    for (b, g) in picked:
+        K64 = inputs.to_f64(K[b, g])[None, None]
+        ob, on, _ = orc.quantize_keys(K64[:, :, :pos], S64)             # the oracle's cache before the step
+        cb = np.zeros((1, 1, w.n, w.m // 8), dtype=np.uint8); cn = np.zeros((1, 1, w.n), dtype=np.float16)
+        cb[:, :, :pos] = ob; cn[:, :, :pos] = on
+        bits_d[b, g, :pos] = torch.from_numpy(ob[0, 0]).to(DEV)         # both sides start from the oracle's codes
+        nu_d[b, g, :pos] = torch.from_numpy(on[0, 0]).to(DEV)
+        refs[(b, g)] = orc.decode_step(Q64[b:b + 1, g * G:(g + 1) * G], S64, cb, cn,
+                                       inputs.to_f64(V[b, g])[None, None], K64[:, :, pos:pos + 1], pos, w.scale)[0]
+    out = qjl.qjl_decode_step(Q, K[:, :, pos:pos + 1].contiguous(), S, bits_d, nu_d, V, pos, w.scale).cpu().numpy()
+    worst = 0.0
+    for (b, g), ref in refs.items():
+        worst = max(worst, assert_attention(out[b, g * G:(g + 1) * G], ref))
+        K64 = inputs.to_f64(K[b, g, pos:pos + 1])[None, None]
+        bad, _, _ = bits_report(bits_d[b, g, pos:pos + 1].cpu().numpy()[None, None], K64, S64)
+        assert bad == 0
+        assert_norms(nu_d[b, g, pos:pos + 1].cpu().numpy()[None, None], K64)
+    # every head's new row was written, and is what the bulk quantizer gives
+    ref_b, ref_n = qjl.qjl_quantize_keys(K[:, :, pos:pos + 1].contiguous(), S)
+    assert torch.equal(nu_d[:, :, pos:pos + 1], ref_n)
+    assert float((bits_d[:, :, pos:pos + 1] != ref_b).float().mean()) < 1e-3      # near-zero projections may differ
+    say(f"  worst attention error over {len(refs) * G} heads: {worst:.3g}")
+
+
 def test_full_size_prefill_quantize_sampled():
     """Config 4 at full size (2,097,152 keys, m = 512): sampled rows against the oracle,
     plus whole-tensor properties (norm range, bit balance)."""
