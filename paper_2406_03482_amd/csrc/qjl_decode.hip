@@ -298,8 +298,11 @@ decode_kernel(decode_args a) {
   VT v[VD];
   // V loads requested before the tables are built: enough to keep HBM busy
   // meanwhile, few enough that the rows of S (requested just before them, and
-  // on the critical path) are not held up behind them
-  constexpr int VP = 4;
+  // on the critical path) are not held up behind them.  Eight for one or two
+  // query heads (4096 keys x 32 heads: 9.9 us against 10.1 with four, 14 with
+  // twelve); four where more work sits between the loads and the tables (four
+  // heads; the new key's projection of a streaming step: 10.9 us against 14.6).
+  constexpr int VP = (GT == 4 || AP) ? 4 : 8;
   // row (4i + r) of the block starting at key kb: uniform base pointer + a
   // 32-bit lane offset, the row clamped to the last key of the chunk
   auto issue_v = [&](int slot, int i, int kb, int last_row) {   // row pass i of block kb -> v[slot]
