@@ -12,7 +12,11 @@
  *
  * General rules for every call
  *   - All data pointers are DEVICE pointers owned by the caller; the library
- *     allocates nothing and keeps no state between calls.  Tensors are dense,
+ *     allocates nothing.  Between calls it remembers only attributes of the
+ *     devices it has run on (compute-unit count, "LDS limit of this kernel
+ *     already raised"), per device ordinal, in atomics: calls from several
+ *     host threads and on several devices are safe, and no result depends on
+ *     that memory.  No environment variable is read.  Tensors are dense,
  *     row-major, with exactly the shapes stated below.  Pointers must be
  *     16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -24,7 +28,8 @@
  *   - Code layout (fixed, shared by all calls): projection i of a key is bit
  *     i%8 of byte i/8 (equivalently bit i%32 of little-endian 32-bit word
  *     i/32); bit 1 means (S k)_i >= 0, i.e. sign +1 (sign(0) := +1).
- *     Norms are IEEE binary16, round-to-nearest-even of the fp32 norm.
+ *     Norms are IEEE binary16, round-to-nearest-even of the fp32 norm; a
+ *     norm above 65504 becomes infinity and the softmax over such a row NaN.
  */
 #ifndef QJL_H_
 #define QJL_H_
@@ -142,6 +147,28 @@ int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S,
                          void* stream);
 
 /*
+ * For tests and tuning: how qjl_decode_attention (m_out = 0) or
+ * qjl_decode_attention_dual (m_out > 0) would cut the context of this shape.
+ * splits = 0: the library's own choice; splits > 0: that many chunks, clamped
+ * to at most 512 and to at least one 64-key block per wave.  plan_out (host,
+ * may be NULL) receives {query heads per workgroup, chunks, keys per chunk}.
+ * Returns the workspace bytes of that plan (0: invalid or unsupported shape).
+ * The bytes never decrease when shape->n grows.  Host only.
+ */
+size_t qjl_decode_plan(const qjl_shape* shape, int m_out, int splits, int32_t* plan_out);
+
+/*
+ * For tests and tuning: qjl_decode_attention with the number of context chunks
+ * fixed by the caller (splits >= 1, clamped as in qjl_decode_plan; workspace
+ * of at least qjl_decode_plan(shape, 0, splits, NULL) bytes).  The result
+ * equals qjl_decode_attention's up to fp32 rounding (Eq. (1)-(2) do not depend
+ * on how the sum over j is cut).
+ */
+int qjl_decode_attention_splits(const qjl_shape* shape, int splits, const void* Q, const void* S,
+                                const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * qjl_decode_attention, plus kernel timing without a profiler: the two
  * caller-owned events (hipEvent_t passed as void*, created with timing
  * enabled; either may be NULL) receive the start and the stop timestamp of
@@ -203,8 +230,11 @@ int qjl_make_dual_sketch(const qjl_shape* shape, int m_out, const void* S_in, co
  * Algorithm 1 steps 3-4, twice per key: bits[B,Hkv,n,(m+m_out)/8] <- packed
  * sign(S_dual k) (same bit order as qjl_quantize_keys), norms_in[B,Hkv,n] <-
  * ||k without its head's outlier channels||, norms_out[B,Hkv,n] <- ||those
- * channels of k||, both binary16.  (m+m_out) % 32 == 0.  Channel entries
- * outside [0,d) are clamped into range.
+ * channels of k||, both binary16 (each summed over its own coordinates).
+ * (m+m_out) % 32 == 0.  Channel entries outside [0,d) are ignored and a
+ * channel listed twice counts once, as in qjl_make_dual_sketch.  A norm above
+ * 65504 is stored as binary16 infinity, and a decode step over such a row
+ * yields NaN: keys must be scaled to stay below that.
  */
 int qjl_quantize_keys_dual(const qjl_shape* shape, int m_out, const void* K, const void* S_dual,
                            const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
@@ -277,7 +307,7 @@ int qjl_append_keys(const qjl_shape* shape, int pos, int count, const void* K_ne
  * caches, then out[B,Hq,d] <- attention of Q[B,Hq,d] over rows 0..pos
  * (Algorithm 1 EstimateScores + Eq. (1)).  Row `pos` of V[B,Hkv,n,d] must
  * already hold the new token's value.  Workspace:
- * qjl_decode_workspace_bytes(shape) covers every pos.  For 16-bit types the
+ * qjl_decode_workspace_bytes(shape), taken at the capacity, covers every pos.  For 16-bit types the
  * key is quantized inside the attention kernel (one launch less than
  * qjl_append_keys + qjl_decode_attention); the cache row is written by that
  * kernel and is complete when the call's work on `stream` is.

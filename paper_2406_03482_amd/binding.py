@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_workspace_bytes.argtypes = [sp]
     L.qjl_decode_attention.restype = ctypes.c_int
     L.qjl_decode_attention.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_decode_plan.restype = ctypes.c_size_t
+    L.qjl_decode_plan.argtypes = [sp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+    L.qjl_decode_attention_splits.restype = ctypes.c_int
+    L.qjl_decode_attention_splits.argtypes = [sp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.qjl_decode_attention_timed.restype = ctypes.c_int
     L.qjl_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     ip = ctypes.c_int
@@ -195,13 +199,22 @@ def qjl_decode_workspace_bytes(batch: int, q_heads: int, kv_heads: int, n: int, 
     return int(lib().qjl_decode_workspace_bytes(ctypes.byref(sh)))
 
 
+def qjl_decode_plan(batch: int, q_heads: int, kv_heads: int, n: int, d: int, m: int, m_out: int = 0,
+                    splits: int = 0, dtype: torch.dtype = torch.bfloat16):
+    """(workspace bytes, query heads per workgroup, chunks, keys per chunk) of the decode call's plan.  Host only."""
+    sh = _shape(batch, q_heads, kv_heads, n, d, m, _DTYPE_TAG[dtype])
+    out = (ctypes.c_int32 * 3)()
+    total = int(lib().qjl_decode_plan(ctypes.byref(sh), m_out, splits, out))
+    return total, int(out[0]), int(out[1]), int(out[2])
+
+
 def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor,
                          V: torch.Tensor, scale: float = 1.0, out: Optional[torch.Tensor] = None,
                          workspace: Optional[torch.Tensor] = None,
-                         events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
+                         events: Optional[Tuple[int, int]] = None, splits: int = 0) -> torch.Tensor:
     """One decode step: Q[B,Hq,d], S[m,d], bits, norms, V[B,Hkv,n,d] -> float32 [B,Hq,d].
     `events` = (hipEvent_t before, hipEvent_t after) as integers selects
-    qjl_decode_attention_timed."""
+    qjl_decode_attention_timed; `splits` > 0 selects qjl_decode_attention_splits."""
     B, Hq, d = Q.shape
     _, Hkv, n, _ = V.shape
     m = S.shape[0]
@@ -209,7 +222,7 @@ def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, n
         raise ValueError("Q, S and V must share one dtype")
     if tuple(bits.shape) != (B, Hkv, n, m // 8) or tuple(norms.shape) != (B, Hkv, n):
         raise ValueError("bits/norms do not match V and S")
-    need = qjl_decode_workspace_bytes(B, Hq, Hkv, n, d, m, Q.dtype)
+    need = qjl_decode_plan(B, Hq, Hkv, n, d, m, 0, splits, Q.dtype)[0]
     if workspace is None:
         workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
     if out is None:
@@ -218,7 +231,9 @@ def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, n
     args = (ctypes.byref(sh), _dev(Q, "Q"), _dev(S, "S"), _dev(bits, "bits"), _dev(norms, "norms"),
             _dev(V, "V"), _dev(out, "out"), _dev(workspace, "workspace"),
             workspace.numel() * workspace.element_size(), _stream(Q))
-    if events is None:
+    if splits > 0:
+        _check("qjl_decode_attention_splits", lib().qjl_decode_attention_splits(args[0], splits, *args[1:]))
+    elif events is None:
         _check("qjl_decode_attention", lib().qjl_decode_attention(*args))
     else:
         _check("qjl_decode_attention_timed", lib().qjl_decode_attention_timed(*args, events[0], events[1]))

@@ -87,11 +87,38 @@ size_t qjl_decode_workspace_bytes(const qjl_shape* shape) {
   return plan.total;
 }
 
+size_t qjl_decode_plan(const qjl_shape* shape, int m_out, int splits, int32_t* plan_out) {
+  if (check_shape(shape) != QJL_OK || m_out < 0 || splits < 0) return 0;
+  decode_plan plan;
+  if (!plan_decode(*shape, m_out, &plan, splits)) return 0;
+  if (plan_out) {
+    plan_out[0] = plan.gt;
+    plan_out[1] = plan.nsplit;
+    plan_out[2] = plan.chunk;
+  }
+  return plan.total;
+}
+
 int qjl_decode_attention(const qjl_shape* shape, const void* Q, const void* S, const uint8_t* bits,
                          const uint16_t* norms, const void* V, float* out, void* workspace,
                          size_t workspace_bytes, void* stream) {
   return qjl_decode_attention_timed(shape, Q, S, bits, norms, V, out, workspace, workspace_bytes,
                                     stream, nullptr, nullptr);
+}
+
+int qjl_decode_attention_splits(const qjl_shape* shape, int splits, const void* Q, const void* S,
+                                const uint8_t* bits, const uint16_t* norms, const void* V, float* out,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(V) || !ptr_ok(out) || splits < 1)
+    return QJL_ERR_INVALID_ARG;
+  decode_plan plan;
+  if (!plan_decode(*shape, 0, &plan, splits)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, 0, out, workspace,
+                       static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void* S,

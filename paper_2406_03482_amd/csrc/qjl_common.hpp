@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "qjl.h"
 
 namespace qjl {
@@ -162,7 +164,7 @@ struct decode_plan {
 // code is sh.m + m_out bits of two independent instances with a norm each, and S
 // holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).  vscale != nullptr: V holds
 // vbits-bit value codes (2, 4 or 8) with a binary16 scale and zero point per token.
-bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan);
+bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_splits = 0);
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
                   const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
@@ -175,5 +177,6 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
 int launch_append_keys(const qjl_shape& sh, const void* K_new, int t, int pos, const void* S, uint8_t* bits,
                        uint16_t* norms, hipStream_t st);
 int device_cu_count();
+int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done);
 
 }  // namespace qjl

@@ -14,14 +14,15 @@
 #include "qjl_lut.hpp"
 
 #include <hip/hip_ext.h>
+#include <atomic>
 #include <type_traits>
-#include <stdlib.h>
 
 namespace qjl {
 namespace {
 
 constexpr int kD = 128;          // head dimension this kernel is written for
 constexpr int kPartStride = 132; // floats per partial record: max, sum, 2 pad, o[128]
+constexpr int kMaxSplits = 512;  // most chunks a context is ever cut into (combine_kernel keeps that many records' heads in LDS)
 
 // LDS bytes of one workgroup: S q (gt*m floats), 4-bit tables (4*gt*m), byte
 // tables (32*gt*m).  Everything else aliases onto tables that are dead by then.
@@ -544,7 +545,7 @@ decode_kernel(decode_args a) {
 // with up to 16 chunks costs a single round trip to memory.
 __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict__ part,
                                                          float* __restrict__ out, int nsplit) {
-  __shared__ float s_m[512], s_l[512], s_z[512];   // per chunk: running max, sum, zero-point sum (nsplit <= 512)
+  __shared__ float s_m[kMaxSplits], s_l[kMaxSplits], s_z[kMaxSplits];   // per chunk: running max, sum, zero-point sum
   __shared__ float s_o[kD], s_lsum, s_zsum;
   const size_t head = blockIdx.x;
   const int tid = threadIdx.x;
@@ -590,15 +591,11 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
 template <typename T, int GT, int MW, int MWB, int VB, bool AP>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
-  static bool attr_set = false;
+  static std::atomic<uint64_t> lds_set{0};             // per kernel instantiation: devices whose limit is raised
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes, VB > 0);
   const size_t lds = decode_lds_bytes(GT, MW * 32) + (AP ? (MW * 32 + MW + 8) * sizeof(float) : 0);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_status(e);
-    attr_set = true;
-  }
+  int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP>), lds, lds_set);
+  if (rc_lds != QJL_OK) return rc_lds;
   const long pairs = (long)sh.batch * sh.kv_heads;
   if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
@@ -673,22 +670,51 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
+// Compute units of the current device.  The only thing the library remembers
+// between calls are such device attributes, per device ordinal, in atomics:
+// a value is written once and two threads that race write the same value.
 int device_cu_count() {
-  static int cached = 0;
-  if (cached > 0) return cached;
+  static std::atomic<int> cached[64];
   int dev = 0, cus = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
-    cached = cus;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 256;  // MI355X; used when no device is visible (host-only callers)
+  }
+  const bool slot = dev >= 0 && dev < 64;
+  if (slot) {
+    cus = cached[dev].load(std::memory_order_relaxed);
+    if (cus > 0) return cus;
+  }
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) {
+    if (slot) cached[dev].store(cus, std::memory_order_relaxed);
     return cus;
   }
   (void)hipGetLastError();
-  return 256;  // MI355X; used when no device is visible (host-only callers)
+  return 256;
+}
+
+// Kernels with more than 64 KB of dynamic LDS need their limit raised once per
+// device.  `done` has one bit per device ordinal; setting the attribute twice
+// is harmless, so two threads that race both set it.
+int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hip_status(hipErrorInvalidDevice);
+  const bool slot = dev >= 0 && dev < 64;
+  if (slot && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return QJL_OK;
+  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return hip_status(e);
+  if (slot) done.fetch_or(uint64_t{1} << dev, std::memory_order_release);
+  return QJL_OK;
 }
 
 // How the context is cut up.  One "unit" is a (batch, kv head, group of GT
 // query heads); it gets nsplit workgroups of `chunk` keys each.
-bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
+// force_splits > 0 fixes the number of chunks (tests and tuning); it is clamped
+// like the automatic choice.  The workspace is sized from the split count before
+// the chunk length is rounded up to whole 64-key blocks: that count never
+// decreases when n grows, so the workspace for a cache's capacity covers every
+// shorter context (the rounded count is not monotonic in n).
+bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_splits) {
   if (sh.d != kD) return false;
   if (m_out == 0) {
     if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
@@ -718,13 +744,11 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
   long nsplit = (slots + units - 1) / units;
   const long min_chunk = 64L * decode_waves(gt, mt, sh.dtype == QJL_F32 ? 4 : 2);  // one 64-key block per wave
   long max_split = ((long)sh.n + min_chunk - 1) / min_chunk;
+  if (force_splits > 0) nsplit = force_splits;
   if (nsplit > max_split) nsplit = max_split;
-  if (nsplit > 512) nsplit = 512;
-  if (const char* e = getenv("QJL_DECODE_SPLITS")) {  // tuning knob for experiments
-    long v = atol(e);
-    if (v >= 1 && v <= 4096) nsplit = v;
-  }
+  if (nsplit > kMaxSplits) nsplit = kMaxSplits;
   if (nsplit < 1) nsplit = 1;
+  const long records = nsplit;                      // upper bound of the rounded count below
   long chunk = ((long)sh.n + nsplit - 1) / nsplit;
   chunk = (chunk + 63) / 64 * 64;
   nsplit = ((long)sh.n + chunk - 1) / chunk;
@@ -733,7 +757,7 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan) {
   plan->chunk = (int)chunk;
   size_t off = 0;
   plan->off_part = off;
-  off = align_up(off + (size_t)sh.batch * sh.q_heads * nsplit * kPartStride * sizeof(float), 256);
+  off = align_up(off + (size_t)sh.batch * sh.q_heads * records * kPartStride * sizeof(float), 256);
   plan->total = off;
   return true;
 }

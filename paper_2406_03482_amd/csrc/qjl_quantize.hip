@@ -55,6 +55,33 @@ template <typename T> __device__ __forceinline__ float elem_to_float(uint16_t x)
 template <> __device__ __forceinline__ float elem_to_float<bf16_t>(uint16_t x) { return bf16_bits_to_float(x); }
 template <> __device__ __forceinline__ float elem_to_float<f16_t>(uint16_t x) { return f16_bits_to_float(x); }
 
+// Outlier channels of a head as a bit mask over its 128 coordinates: entries
+// outside [0, 128) are ignored and a channel listed twice counts once -- the
+// rule of every quantize path and of the stacked sketch.
+struct chan_mask { uint32_t w[4]; };
+__device__ __forceinline__ chan_mask make_chan_mask(const int32_t* channels, int count) {
+  chan_mask cm = {{0u, 0u, 0u, 0u}};
+  for (int t = 0; t < count; ++t) {
+    const int c = channels[t];
+    if (c >= 0 && c < 128) cm.w[c >> 5] |= 1u << (c & 31);
+  }
+  return cm;
+}
+// sums of squares of the eight elements of one 16-byte chunk, split by the chunk's 8 mask bits
+template <typename T> __device__ __forceinline__ void sumsq8_split(const uint32_t (&w)[4], uint32_t mb, float& in,
+                                                                   float& out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float a, b;
+    unpack2<T>(w[i], a, b);
+    const bool oa = (mb >> (2 * i)) & 1u, ob = (mb >> (2 * i + 1)) & 1u;
+    out = fmaf(a, oa ? a : 0.f, out);
+    in = fmaf(a, oa ? 0.f : a, in);
+    out = fmaf(b, ob ? b : 0.f, out);
+    in = fmaf(b, ob ? 0.f : b, in);
+  }
+}
+
 constexpr int kTok = 64;        // keys per tile: two N = 32 MFMA sub-tiles
 constexpr int kRowU4 = 17;      // LDS row pitch in 16-byte units: 256 B of key + 16 B pad
 
@@ -130,7 +157,8 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   constexpr int WPT = CW * PPW / 32;      // code words per key written by this workgroup
   __shared__ uint4 kbuf[2][kTok * kRowU4];
   __shared__ uint4 obuf[2][kTok * WPT / 4];
-  __shared__ float nsq[2][kTok];           // squared norms of the tile's keys
+  __shared__ float nsq[2][kTok];           // squared norms of the tile's keys (DUAL: without the outlier channels)
+  __shared__ float nsq_out[DUAL ? 2 : 1][kTok];   // DUAL: squared norms of the outlier channels
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -181,18 +209,39 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
       }
     }
   };
+  // DUAL: the 8 mask bits of this thread's 16-byte column; the two parts are summed
+  // separately (a difference of the whole and the outlier part would cancel)
+  uint32_t col_mask = 0;
+  if constexpr (DUAL) {
+    const chan_mask cm = make_chan_mask(channels, count);
+    col_mask = (cm.w[lcol >> 2] >> (8 * (lcol & 3))) & 0xFFu;
+  }
   auto stage_tile = [&](int buf) {
-    float ss[4];
+    float ss[4], so[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       kbuf[buf][(lrow + 16 * u) * kRowU4 + lcol] = pre[u];
-      ss[u] = sumsq8<T>(pre[u]);
+      if (DUAL && col_mask != 0) {
+        const uint32_t w[4] = {pre[u].x, pre[u].y, pre[u].z, pre[u].w};
+        ss[u] = 0.f;
+        sumsq8_split<T>(w, col_mask, ss[u], so[u]);
+      } else {
+        ss[u] = sumsq8<T>(pre[u]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) ss[u] = row16_sum(ss[u]);   // the 16 lanes of a DPP row hold one key
+    if constexpr (DUAL) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) so[u] = row16_sum(so[u]);
+    }
     if (lcol == 0) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) nsq[buf][lrow + 16 * u] = ss[u];
+      if constexpr (DUAL) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) nsq_out[buf][lrow + 16 * u] = so[u];
+      }
     }
   };
 
@@ -216,18 +265,10 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     // previous iteration's barrier and stay there until this iteration's barrier
     if (blockIdx.y == 0 && wave == 3) {               // one wave, one key per lane: a single square root
       const long trow = (long)tile * kTok + lane;
-      float sq_all = nsq[buf][lane];
       if constexpr (DUAL) {
-        const uint16_t* krow = reinterpret_cast<const uint16_t*>(kbuf[buf]) + lane * (kRowU4 * 8);
-        float sq_out = 0.f;
-        for (int t = 0; t < count; ++t) {
-          const float x = elem_to_float<T>(krow[min(max(channels[t], 0), 127)]);
-          sq_out = fmaf(x, x, sq_out);
-        }
-        if (trow < rows) norms_out[trow] = float_to_f16_bits(sqrtf(sq_out));
-        sq_all = fmaxf(sq_all - sq_out, 0.f);
+        if (trow < rows) norms_out[trow] = float_to_f16_bits(sqrtf(nsq_out[buf][lane]));
       }
-      if (trow < rows) norms[trow] = float_to_f16_bits(sqrtf(sq_all));
+      if (trow < rows) norms[trow] = float_to_f16_bits(sqrtf(nsq[buf][lane]));
     }
 
     // ---- MFMA phase.  The tile's work is cut into NU units of two accumulator
@@ -392,10 +433,11 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   uint32_t omask = 0;
   uint32_t smask = 0;
   if constexpr (DUAL) {
-    for (int t = 0; t < count; ++t) {
-      const int c = min(max(channels[t], 0), 127);
-      smask |= 1u << (c >> 5);
-      if (((c >> 3) & 3) == q) omask |= 1u << (8 * (c >> 5) + (c & 7));
+    const chan_mask cm = make_chan_mask(channels, count);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (cm.w[s] != 0) smask |= 1u << s;
+      omask |= ((cm.w[s] >> (8 * q)) & 0xFFu) << (8 * s);
     }
   }
 
@@ -483,32 +525,25 @@ quantize_slds_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     // ---- norms: a key's elements are split over lanes (0..3, j)
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      float ss = 0.f;
+      // DUAL: ss is the inlier part alone; the two parts are summed separately (a
+      // difference of the whole and the outlier part would cancel for large outliers)
+      float ss = 0.f, so = 0.f;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ss += sumsq8v<T>(cur[c][s]);
+      for (int s = 0; s < 4; ++s) {
+        if (DUAL && ((smask >> s) & 1u)) {            // uniform
+          const uint32_t w[4] = {cur[c][s][0], cur[c][s][1], cur[c][s][2], cur[c][s][3]};
+          sumsq8_split<T>(w, (omask >> (8 * s)) & 0xFFu, ss, so);
+        } else {
+          ss += sumsq8v<T>(cur[c][s]);
+        }
+      }
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
       const long row = row0 + c * 16 + j;
       if constexpr (DUAL) {
-        float so = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          if ((smask >> s) & 1u) {                    // uniform
-            const uint32_t mb = (omask >> (8 * s)) & 0xFFu;
-            const uint32_t w[4] = {cur[c][s][0], cur[c][s][1], cur[c][s][2], cur[c][s][3]};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              float a, b;
-              unpack2<T>(w[i], a, b);
-              so = fmaf(a, ((mb >> (2 * i)) & 1u) ? a : 0.f, so);
-              so = fmaf(b, ((mb >> (2 * i + 1)) & 1u) ? b : 0.f, so);
-            }
-          }
-        }
         so += __shfl_xor(so, 16);
         so += __shfl_xor(so, 32);
         if (q == 0 && row < rows) norms_out[row] = float_to_f16_bits(sqrtf(so));
-        ss = fmaxf(ss - so, 0.f);
       }
       if (q == 0 && row < rows) norms[row] = float_to_f16_bits(sqrtf(ss));
     }
@@ -602,17 +637,18 @@ quantize_generic_kernel(const void* __restrict__ K, const void* __restrict__ S, 
   }
   if (tid < ntok) {
     const float* kr = kf + tid * d;
-    float ss = 0.f;
-    for (int t = 0; t < d; ++t) ss = fmaf(kr[t], kr[t], ss);
-    if constexpr (DUAL) {
-      float so = 0.f;
-      for (int t = 0; t < count; ++t) {
-        const float x = kr[min(max(channels[seg * (size_t)count + t], 0), d - 1)];
-        so = fmaf(x, x, so);
+    // DUAL: a coordinate is an outlier if the head's list names it (entries outside
+    // [0, d) match nothing, a repeated entry matches once); the parts are summed separately
+    float ss = 0.f, so = 0.f;
+    for (int t = 0; t < d; ++t) {
+      bool is_out = false;
+      if constexpr (DUAL) {
+        for (int u = 0; u < count; ++u) is_out |= channels[seg * (size_t)count + u] == t;
       }
-      norms_out[r0 + row0 + tid] = float_to_f16_bits(sqrtf(so));
-      ss = fmaxf(ss - so, 0.f);
+      if (is_out) so = fmaf(kr[t], kr[t], so);
+      else ss = fmaf(kr[t], kr[t], ss);
     }
+    if constexpr (DUAL) norms_out[r0 + row0 + tid] = float_to_f16_bits(sqrtf(so));
     norms[r0 + row0 + tid] = float_to_f16_bits(sqrtf(ss));
   }
 }
@@ -649,13 +685,9 @@ int launch_slds(const quant_io& q, hipStream_t st) {
   if (tiles > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   // the sketch, the tile counter, 2 KB per wave to rearrange keys
   constexpr size_t lds = (size_t)NB * 32 * kSPitch * 16 + 16 + 8 * 2048;
-  static bool attr_set = false;           // the kernel needs more than the default 64 KB of LDS
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&quantize_slds_kernel<T, NB, DUAL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_status(e);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_set{0};   // the kernel needs more than the default 64 KB of LDS
+  const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&quantize_slds_kernel<T, NB, DUAL>), lds, lds_set);
+  if (rc_lds != QJL_OK) return rc_lds;
   // one workgroup of eight waves per CU in total, each owning a range of its segment's tiles
   long gx = (device_cu_count() + q.segments - 1) / q.segments;
   if (gx > (tiles + 7) / 8) gx = (tiles + 7) / 8;

@@ -55,14 +55,10 @@ __global__ void __launch_bounds__(256) scores_kernel(scores_args a) {
 
 template <int GT, int MW>
 int launch_t(const qjl_shape& sh, scores_args a, hipStream_t st) {
-  static bool attr_set = false;  // benign race: setting it twice is harmless
+  static std::atomic<uint64_t> lds_set{0};
   const size_t lds = lut_lds_floats<GT>(MW * 32) * sizeof(float);
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scores_kernel<GT, MW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return hip_status(e);
-    attr_set = true;
-  }
+  const int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&scores_kernel<GT, MW>), lds, lds_set);
+  if (rc_lds != QJL_OK) return rc_lds;
   const int G = sh.q_heads / sh.kv_heads;
   a.groups_per_kv = G / GT;
   const long units = (long)sh.batch * sh.kv_heads * a.groups_per_kv;

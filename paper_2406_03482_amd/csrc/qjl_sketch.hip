@@ -106,15 +106,11 @@ int launch_make_sketch(uint64_t seed, int m, int d, int dtype, void* S, hipStrea
 int launch_make_sketch_orthogonal(uint64_t seed, int m, int d, int dtype, void* S, hipStream_t st) {
   if (d > 128) return QJL_ERR_UNSUPPORTED;
   const size_t lds = ((size_t)d * d + 256) * sizeof(double);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipSuccess;
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_F32>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_F16>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_BF16>), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return hip_status(e);
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> set32{0}, set16{0}, setb16{0};
+  int rc = allow_dynamic_lds(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_F32>), 160 * 1024, set32);
+  if (rc == QJL_OK) rc = allow_dynamic_lds(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_F16>), 160 * 1024, set16);
+  if (rc == QJL_OK) rc = allow_dynamic_lds(reinterpret_cast<const void*>(&orth_sketch_kernel<QJL_BF16>), 160 * 1024, setb16);
+  if (rc != QJL_OK) return rc;
   dim3 grid((unsigned)((m + d - 1) / d)), block(256);
   switch (dtype) {
     case QJL_F32: hipLaunchKernelGGL(orth_sketch_kernel<QJL_F32>, grid, block, lds, st, seed, m, d, S); break;

@@ -30,8 +30,9 @@ def _declared_symbols():
 
 def test_header_symbols_are_exported(L):
     names = _declared_symbols()
-    assert names == ["qjl_append_keys", "qjl_decode_attention", "qjl_decode_attention_dual", "qjl_decode_attention_timed",
-                     "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_step",
+    assert names == ["qjl_append_keys", "qjl_decode_attention", "qjl_decode_attention_dual",
+                     "qjl_decode_attention_splits", "qjl_decode_attention_timed",
+                     "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_plan", "qjl_decode_step",
                      "qjl_decode_workspace_bytes",
                      "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_make_sketch_orthogonal", "qjl_outlier_workspace_bytes",
                      "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_quantize_values",
@@ -201,3 +202,42 @@ def test_streaming_entry_points_validate_on_the_host(L):
     assert L.qjl_append_keys(ctypes.byref(d64), 0, 1, ok, ok, ok, ok, None) == UNSUPPORTED
     assert L.qjl_decode_step(ctypes.byref(sh), 100, ok, ok, ok, ok, ok, ok, ok, ok, ctypes.c_size_t(1 << 30), None) == INVALID
     assert L.qjl_decode_step(ctypes.byref(sh), 5, ok, ok, ok, ok, ok, ok, ok, None, ctypes.c_size_t(0), None) == WORKSPACE
+
+
+# ------------------------------------------------------------------ the decode plan (host arithmetic only)
+def _plan(L, splits=0, m_out=0, **kw):
+    sh = _sh(**kw)
+    out = (ctypes.c_int32 * 3)()
+    L.qjl_decode_plan.restype = ctypes.c_size_t
+    total = L.qjl_decode_plan(ctypes.byref(sh), m_out, splits, out)
+    return int(total), int(out[0]), int(out[1]), int(out[2])
+
+
+def test_forced_split_count_is_clamped_to_what_the_merge_kernel_holds(L):
+    """The merge kernel keeps 512 chunk records' heads in LDS: no request may plan more."""
+    for splits in (513, 1000, 4096, 2 ** 30):
+        total, gt, nsplit, chunk = _plan(L, splits=splits, batch=1, q_heads=32, kv_heads=32, n=131072)
+        assert 1 <= nsplit <= 512 and chunk % 64 == 0 and nsplit * chunk >= 131072
+        assert total >= 1 * 32 * nsplit * 132 * 4
+    # and never fewer than one 64-key block per wave
+    total, gt, nsplit, chunk = _plan(L, splits=4096, batch=1, q_heads=8, kv_heads=2, n=5000)
+    assert gt == 4 and nsplit == 10 and chunk == 512
+    assert _plan(L, splits=-1)[0] == 0
+
+
+@pytest.mark.parametrize("kw", [dict(batch=1, q_heads=32, kv_heads=8, n=33000), dict(batch=1, q_heads=1, kv_heads=1, n=70000),
+                                dict(batch=2, q_heads=32, kv_heads=32, n=9999), dict(batch=1, q_heads=6, kv_heads=2, n=20011)])
+def test_workspace_of_the_capacity_covers_every_shorter_context(L, kw):
+    """A streaming generation sizes its workspace once, at the capacity of its caches (qjl_decode_step):
+    the bytes of the plan must never decrease as the context grows, and every plan's records must fit its bytes."""
+    cap = kw["n"]
+    last = 0
+    for n in list(range(1, 2050)) + list(range(2050, cap, 97)) + [cap]:
+        total, gt, nsplit, chunk = _plan(L, **dict(kw, n=n))
+        assert total >= last, (n, total, last)
+        assert total >= kw["batch"] * kw["q_heads"] * nsplit * 132 * 4
+        assert (nsplit - 1) * chunk < n <= nsplit * chunk
+        last = total
+    assert last == _plan(L, **kw)[0]
+    L.qjl_decode_workspace_bytes.restype = ctypes.c_size_t
+    assert L.qjl_decode_workspace_bytes(ctypes.byref(_sh(**kw))) == last
