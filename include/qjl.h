@@ -183,6 +183,28 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
                                float* out, void* workspace, size_t workspace_bytes,
                                void* stream, void* event_before, void* event_after);
 
+/*
+ * For callers that cannot allocate device memory or carry a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): qjl_decode_attention without the workspace arguments.  The
+ * per-chunk records live in a device array inside the library, 4 MiB
+ * (qjl_decode_noalloc_max_bytes(), 7943 (query head, chunk) records) that every
+ * GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing and calls no allocating routine.  A shape whose
+ * qjl_decode_workspace_bytes() exceeds the array is rejected with
+ * QJL_ERR_WORKSPACE (all of this build's benchmark shapes fit: the largest
+ * needs 1.1 MB).  Every call on a GPU uses that GPU's one array, whose contents
+ * are whatever the last call left (nothing needs clearing: each call writes
+ * every record before it reads it): two calls that overlap in time on one GPU
+ * -- different streams, or different threads -- race and must be ordered by the
+ * caller.  Inputs, outputs, result and every other rule as in
+ * qjl_decode_attention.
+ */
+size_t qjl_decode_noalloc_max_bytes(void);
+int qjl_decode_attention_noalloc(const qjl_shape* shape, const void* Q, const void* S,
+                                 const uint8_t* bits, const uint16_t* norms, const void* V,
+                                 float* out, void* stream);
+
 /* ------------------------------------------------------------------------
  * Outlier channels (Section 4.1, "Outliers"; end of Section 1): certain fixed
  * channels of the keys of a head are much larger than the rest; they are

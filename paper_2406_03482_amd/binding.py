@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_plan.argtypes = [sp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
     L.qjl_decode_attention_splits.restype = ctypes.c_int
     L.qjl_decode_attention_splits.argtypes = [sp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_decode_noalloc_max_bytes.restype = ctypes.c_size_t
+    L.qjl_decode_noalloc_max_bytes.argtypes = []
+    L.qjl_decode_attention_noalloc.restype = ctypes.c_int
+    L.qjl_decode_attention_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
     L.qjl_decode_attention_timed.restype = ctypes.c_int
     L.qjl_decode_attention_timed.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     ip = ctypes.c_int
@@ -237,6 +241,26 @@ def qjl_decode_attention(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, n
         _check("qjl_decode_attention", lib().qjl_decode_attention(*args))
     else:
         _check("qjl_decode_attention_timed", lib().qjl_decode_attention_timed(*args, events[0], events[1]))
+    return out
+
+
+def qjl_decode_attention_noalloc(Q: torch.Tensor, S: torch.Tensor, bits: torch.Tensor, norms: torch.Tensor,
+                                 V: torch.Tensor, scale: float, out: torch.Tensor) -> torch.Tensor:
+    """qjl_decode_attention into a caller-provided `out`, with the per-chunk records in the library's own device
+    array: neither this wrapper nor the call allocates."""
+    B, Hq, d = Q.shape
+    _, Hkv, n, _ = V.shape
+    m = S.shape[0]
+    if V.dtype != Q.dtype or S.dtype != Q.dtype:
+        raise ValueError("Q, S and V must share one dtype")
+    if tuple(bits.shape) != (B, Hkv, n, m // 8) or tuple(norms.shape) != (B, Hkv, n):
+        raise ValueError("bits/norms do not match V and S")
+    if tuple(out.shape) != (B, Hq, d) or out.dtype != torch.float32:
+        raise ValueError("out must be float32 [B,Hq,d]")
+    sh = _shape(B, Hq, Hkv, n, d, m, _tag(Q), scale)
+    _check("qjl_decode_attention_noalloc",
+           lib().qjl_decode_attention_noalloc(ctypes.byref(sh), _dev(Q, "Q"), _dev(S, "S"), _dev(bits, "bits"),
+                                              _dev(norms, "norms"), _dev(V, "V"), _dev(out, "out"), _stream(Q)))
     return out
 
 

@@ -23,6 +23,32 @@ int check_shape(const qjl_shape* sh) {
 
 bool ptr_ok(const void* p) { return p != nullptr && aligned16(p); }
 
+// ---- scratch of qjl_decode_attention_noalloc: the per-chunk softmax records, in
+// a device array that exists from the moment the library is loaded on a GPU
+// until the process ends (every GPU holds its own copy at its own address).
+constexpr size_t kScratchBytes = size_t{4} << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's
+// name is only a handle for hipGetSymbolAddress, never an address: the pointer
+// obtained here is what kernels, copies and fills receive.  Looked up once per
+// device ordinal (with that device current) and remembered.
+int scratch_of_current_device(void** out) {
+  static std::atomic<void*> known[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hip_status(hipErrorInvalidDevice);
+  const bool slot = dev >= 0 && dev < 64;
+  void* ptr = slot ? known[dev].load(std::memory_order_acquire) : nullptr;
+  if (ptr == nullptr) {
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_status(e);
+    if (ptr == nullptr) return QJL_ERR_HIP;
+    if (slot) known[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return QJL_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -136,6 +162,25 @@ int qjl_decode_attention_timed(const qjl_shape* shape, const void* Q, const void
   return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, 0, out, workspace,
                        static_cast<hipStream_t>(stream), static_cast<hipEvent_t>(event_before),
                        static_cast<hipEvent_t>(event_after));
+}
+
+size_t qjl_decode_noalloc_max_bytes(void) { return kScratchBytes; }
+
+int qjl_decode_attention_noalloc(const qjl_shape* shape, const void* Q, const void* S, const uint8_t* bits,
+                                 const uint16_t* norms, const void* V, float* out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(Q) || !ptr_ok(S) || !ptr_ok(bits) || !ptr_ok(norms) || !ptr_ok(V) || !ptr_ok(out))
+    return QJL_ERR_INVALID_ARG;
+  decode_plan plan;
+  if (!plan_decode(*shape, 0, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (plan.total > kScratchBytes) return QJL_ERR_WORKSPACE;   // the shape needs more records than the array holds
+  void* ws = nullptr;
+  rc = scratch_of_current_device(&ws);
+  if (rc != QJL_OK) return rc;
+  // nothing to clear: every record that the merge kernel reads is written by this call's attention kernel first
+  return launch_decode(*shape, 0, plan, Q, S, bits, norms, nullptr, V, nullptr, nullptr, 0, 0, out, ws,
+                       static_cast<hipStream_t>(stream), nullptr, nullptr);
 }
 
 size_t qjl_outlier_workspace_bytes(const qjl_shape* shape) {
