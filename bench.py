@@ -1,22 +1,30 @@
 #!/usr/bin/env python3
 """Benchmark of the QJL hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-extra] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-extra] [--no-cpu]
 
-A "step" is one decode step of the Llama-2-7B-shaped workload (batch 1, 32
-heads, d = 128, m = 256, context 4096; keys already quantized and everything
-resident in HBM): project the query, estimate all scores, softmax, aggregate
-the bf16 values -- one call of qjl_decode_attention.  The headline `value` is
-keys (= batch x kv-head x token triples) per second over exactly K steps; the
-steps are replayed from a HIP graph so that the host's launch cost does not
-hide the GPU time (the eager rate is reported next to it).
+A "step" is one decode step of the long-context workload (batch 4, 32 heads,
+d = 128, m = 256, context 32768: 4,194,304 cached keys, 1.2 GB of codes, norms
+and values; the largest of the configurations, all of it resident in HBM):
+project the query, estimate all scores, softmax, aggregate the bf16 values --
+one call of qjl_decode_attention.  The headline `value` is keys (= batch x
+kv-head x token triples) per second over exactly K steps; the steps are
+replayed from a HIP graph so that the host's launch cost does not hide the GPU
+time (the eager rate is reported next to it).
 
-The `roofline` object is for the attention kernel of that step: algorithmic
-bytes per launch (290 B per key: 32 B code + 2 B norm + 256 B values) over the
-kernel's mean duration measured with HIP events recorded around the kernel
-itself (qjl_decode_attention_timed).  `other_workloads` repeats the
-measurement for the long-context, GQA and prefill-quantize configurations.
-`cpu_baseline` times the CPU oracle on the same workload.
+`roofline` is for the attention kernel of that step: algorithmic bytes per
+launch (290 B per key: 32 B code + 2 B norm + 256 B values) over the kernel's
+mean duration, taken from the kernel's own start/stop timestamps
+(qjl_decode_attention_timed).  `ceilings` holds what a plain streaming read and
+a back-to-back bf16 MFMA loop reach on this chip in the same run
+(libqjl_ceilings.so), and every roofline carries `frac_of_ceiling` next to
+`frac`.  `other_workloads` repeats the measurement for the other decode
+configurations (those that fit the 256 MB last-level cache also with rotating
+copies of the cache, `*_cold`), the prefill quantizer and the widened rows.
+`cpu_baseline` times the CPU oracle on a bounded sample of the headline
+workload (`cpu_baselines_other`: GQA decode and prefill quantize), and
+`sign_bits` counts the near-zero sign decisions on which the GPU's code of that
+sample differs from the oracle's.
 """
 from __future__ import annotations
 
@@ -33,6 +41,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak, published
+COLD_BYTES = 640 << 20          # rotating copies of a cache add up to at least this (last-level cache: 256 MB)
+CEIL = {}                       # filled by measure_ceilings(): name -> rate
 
 
 class HipEvents:
@@ -136,10 +146,64 @@ def run_decode(qjl, t, w, events=None):
                              workspace=t["ws"], events=events)
 
 
-def time_decode(qjl, ev, w, t, steps, warmup, graph_batch=None):
-    """Returns dict(ms_graph, ms_eager, kernel_ms) for one workload."""
+def cache_sets(t, w):
+    """Rotating copies of everything a decode step streams (codes, norms, values): enough of them that the last-level
+    cache (256 MB) cannot hold what the next step reads.  The first set is the original."""
     import torch
-    stream = torch.cuda.current_stream().cuda_stream
+    big = [k for k in ("bits", "norms", "norms_out", "V", "vcodes", "vscale", "vzero") if t.get(k) is not None]
+    set_bytes = sum(t[k].numel() * t[k].element_size() for k in big)
+    count = max(3, -(-COLD_BYTES // set_bytes))
+    sets = [t]
+    for _ in range(count - 1):
+        c = dict(t)
+        for k in big:
+            c[k] = t[k].clone()
+        sets.append(c)
+    torch.cuda.synchronize()
+    return sets, set_bytes
+
+
+def graph_time(run, steps, warmup, gb):
+    """ms per step over exactly `steps` steps replayed from a HIP graph that holds `gb` of them (run(i) = step i)."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(gb):
+            run(i)
+    for _ in range(max(1, warmup // gb)):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps // gb):
+        g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_time(qjl, ev, w, sets, count):
+    """Mean and median duration (ms) of the attention kernel alone: events recorded around it inside the call."""
+    import torch
+    pairs = [(ev.create(), ev.create()) for _ in range(count)]
+    for i, (a, b) in enumerate(pairs):
+        run_decode(qjl, sets[i % len(sets)], w, events=(a, b))
+    torch.cuda.synchronize()
+    durs = sorted(ev.elapsed_ms(a, b) for a, b in pairs)
+    for a, b in pairs:
+        ev.destroy(a)
+        ev.destroy(b)
+    return sum(durs) / len(durs), durs[len(durs) // 2]
+
+
+def time_decode(qjl, ev, w, t, steps, warmup, graph_batch=None, cold=False):
+    """Returns dict(ms_graph, ms_eager, kernel_ms, ...) for one workload; with `cold` also the same figures with
+    the caches rotated over copies that together exceed the last-level cache."""
+    import torch
     for _ in range(warmup):
         run_decode(qjl, t, w)
     torch.cuda.synchronize()
@@ -151,45 +215,39 @@ def time_decode(qjl, ev, w, t, steps, warmup, graph_batch=None):
     ms_eager = (time.perf_counter() - t0) * 1e3 / steps
     # ---- HIP graph holding `gb` steps, replayed steps/gb times (exactly `steps` steps)
     gb = graph_batch or next(g for g in (50, 25, 20, 10, 5, 4, 2, 1) if steps % g == 0)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        run_decode(qjl, t, w)
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        for _ in range(gb):
-            run_decode(qjl, t, w)
-    for _ in range(max(1, warmup // gb)):
-        g.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps // gb):
-        g.replay()
-    torch.cuda.synchronize()
-    ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    ms_graph = graph_time(lambda i: run_decode(qjl, t, w), steps, warmup, gb)
+    r = dict(ms_graph=ms_graph, ms_eager=ms_eager, graph_batch=gb)
     if w.stream:        # no kernel-timestamp variant of this call: the roofline figure uses the whole step
-        return dict(ms_graph=ms_graph, ms_eager=ms_eager, kernel_ms=ms_graph, kernel_ms_median=ms_graph, graph_batch=gb)
-    # ---- the attention kernel alone: events recorded around it inside the library call
-    nk = min(steps, 200)
-    pairs = [(ev.create(), ev.create()) for _ in range(nk)]
-    for a, b in pairs:
-        run_decode(qjl, t, w, events=(a, b))
-    torch.cuda.synchronize()
-    durs = sorted(ev.elapsed_ms(a, b) for a, b in pairs)
-    for a, b in pairs:
-        ev.destroy(a)
-        ev.destroy(b)
-    kernel_ms = sum(durs) / len(durs)
-    return dict(ms_graph=ms_graph, ms_eager=ms_eager, kernel_ms=kernel_ms, kernel_ms_median=durs[len(durs) // 2],
-                graph_batch=gb)
+        r.update(kernel_ms=ms_graph, kernel_ms_median=ms_graph)
+        return r
+    r["kernel_ms"], r["kernel_ms_median"] = kernel_time(qjl, ev, w, [t], min(steps, 200))
+    if cold:
+        sets, set_bytes = cache_sets(t, w)
+        gbc = max(gb, len(sets))
+        steps_c = max(gbc, steps // gbc * gbc)
+        r["ms_graph_cold"] = graph_time(lambda i: run_decode(qjl, sets[i % len(sets)], w), steps_c, warmup, gbc)
+        r["kernel_ms_cold"], r["kernel_ms_cold_median"] = kernel_time(qjl, ev, w, sets, min(steps, 200))
+        r["cold_sets"], r["cold_bytes"] = len(sets), len(sets) * set_bytes
+        del sets
+    return r
+
+
+def read_ceiling(nbytes, cold):
+    """The streaming-read rate (GB/s) measured at the size closest to nbytes."""
+    if not CEIL:
+        return None
+    if nbytes >= 700e6:
+        return CEIL.get("read_1200MB_GBs")
+    if nbytes >= 150e6:
+        return CEIL.get("read_300MB_cold_GBs" if cold else "read_300MB_GBs")
+    return CEIL.get("read_38MB_cold_GBs" if cold else "read_38MB_GBs")
 
 
 def decode_record(w, r):
     algo_bytes = decode_bytes_per_key(w) * w.key_heads
     achieved = algo_bytes / (r["kernel_ms"] * 1e-3) / 1e9
-    return {
+    ceil = read_ceiling(algo_bytes, False)
+    rec = {
         "workload": w.name,
         "metric": "decode keys/s/GPU",
         "value": w.key_heads / (r["ms_graph"] * 1e-3),
@@ -197,9 +255,104 @@ def decode_record(w, r):
         "ms_per_step_eager": r["ms_eager"],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": load_traffic(w.name),
+                     "ceiling": ceil, "frac_of_ceiling": achieved / ceil if ceil else None,
                      "kernel": "decode_kernel", "kernel_ms": r["kernel_ms"],
                      "kernel_ms_median": r["kernel_ms_median"], "algorithmic_bytes": algo_bytes},
     }
+    if "ms_graph_cold" in r:        # every step reads a copy of the cache that the last-level cache cannot still hold
+        ach_c = algo_bytes / (r["kernel_ms_cold"] * 1e-3) / 1e9
+        ceil_c = read_ceiling(algo_bytes, True)
+        rec.update({"value_cold": w.key_heads / (r["ms_graph_cold"] * 1e-3), "ms_per_step_cold": r["ms_graph_cold"]})
+        rec["roofline"].update({"achieved_cold": ach_c, "frac_cold": ach_c / HBM_PEAK_GBS,
+                                "kernel_ms_cold": r["kernel_ms_cold"], "kernel_ms_cold_median": r["kernel_ms_cold_median"],
+                                "ceiling_cold": ceil_c, "frac_of_ceiling_cold": ach_c / ceil_c if ceil_c else None,
+                                "cold_sets": r["cold_sets"], "cold_bytes": r["cold_bytes"]})
+    return rec
+
+
+class Ceilings:
+    """libqjl_ceilings.so through ctypes: a streaming read, a copy and an MFMA loop (no part of the method)."""
+
+    def __init__(self):
+        path = os.path.join(ROOT, "paper_2406_03482_amd", "libqjl_ceilings.so")
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2406_03482_amd.build`")
+        L = ctypes.CDLL(path)
+        vp = ctypes.c_void_p
+        L.ceil_stream_read.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp, vp]
+        L.ceil_copy.argtypes = [vp, vp, ctypes.c_size_t, ctypes.c_int, vp]
+        L.ceil_mfma_loop.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+        self.L = L
+
+
+def timed_launches(ev, stream, launch, count, warm):
+    """ms per launch over `count` launches back to back on `stream`, bracketed by two events."""
+    import torch
+    for i in range(warm):
+        launch(i)
+    torch.cuda.synchronize()
+    a, b = ev.create(), ev.create()
+    ev.record(a, stream)
+    for i in range(count):
+        launch(i)
+    ev.record(b, stream)
+    ms = ev.elapsed_ms(a, b) / count
+    ev.destroy(a)
+    ev.destroy(b)
+    return ms
+
+
+def measure_ceilings(ev, dev, quick=False):
+    """What this chip sustains, measured like the kernels themselves: streaming reads of the decode workloads' sizes
+    (warm = the same buffer again and again, cold = rotating buffers adding up to more than the last-level cache) and
+    a loop of nothing but bf16 MFMAs on N(0,1) operands, eight waves per CU, >= 50 launches back to back so that the
+    clock has settled to what the chip holds under matrix load."""
+    import torch
+    C = Ceilings().L
+    stream = torch.cuda.current_stream().cuda_stream
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    out = {}
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    for label, nbytes in (("38MB", 38010880), ("300MB", 304087040), ("1200MB", 1216348160)):
+        nsets = 1 if nbytes > 700e6 else max(3, -(-COLD_BYTES // nbytes))
+        bufs = [torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device=dev, generator=g) for _ in range(nsets)]
+        reps = 20 if quick else (200 if nbytes < 100e6 else 60)
+        # the ceiling is the best of a few launch shapes (workgroups per CU x load kind x access pattern)
+        shapes = [(cus * k, mode) for k in (2, 4, 8, 16) for mode in range(4)]
+        def sweep(pick):
+            best = None
+            for blocks, mode in shapes:
+                ms = timed_launches(ev, stream, lambda i: C.ceil_stream_read(pick(i).data_ptr(), nbytes, blocks, mode, sink.data_ptr(), stream),
+                                    max(10, reps // 4), 3)
+                if best is None or ms < best[0]:
+                    best = (ms, blocks, mode)
+            ms = timed_launches(ev, stream, lambda i: C.ceil_stream_read(pick(i).data_ptr(), nbytes, best[1], best[2], sink.data_ptr(), stream), reps, 5)
+            return min(ms, best[0]), best[1], best[2]
+        ms, blocks, mode = sweep(lambda i: bufs[0])
+        out[f"read_{label}_GBs"] = nbytes / (ms * 1e-3) / 1e9
+        out[f"read_{label}_shape"] = f"{blocks} workgroups, mode {mode}"
+        if nsets > 1:
+            ms, blocks, mode = sweep(lambda i: bufs[i % nsets])
+            out[f"read_{label}_cold_GBs"] = nbytes / (ms * 1e-3) / 1e9
+            out[f"read_{label}_cold_shape"] = f"{blocks} workgroups, mode {mode}"
+        del bufs
+        torch.cuda.empty_cache()
+    frag = torch.randn((8 * 64 * 8,), device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    zeros = torch.zeros_like(frag)
+    flops = ctypes.c_double()
+    iters = 2000 if quick else 6000          # 16 MFMAs per iteration and wave: about 1.5 ms per launch
+    for label, wide, src in (("mfma_16x16x32_TFLOPs", 0, frag), ("mfma_32x32x16_TFLOPs", 1, frag),
+                             ("mfma_16x16x32_zero_operands_TFLOPs", 0, zeros)):
+        ms = timed_launches(ev, stream, lambda i: C.ceil_mfma_loop(src.data_ptr(), wide, iters, cus, sink.data_ptr(), ctypes.byref(flops), stream),
+                            20 if quick else 60, 5)
+        out[label] = flops.value / (ms * 1e-3) / 1e12
+    out["mfma_TFLOPs"] = out["mfma_16x16x32_TFLOPs"]   # the quantizer's instruction and operand statistics
+    out["read_GBs"] = out["read_1200MB_GBs"]
+    out["note"] = ("streaming read with 16-byte loads, nothing written; MFMA loop of eight waves per CU on N(0,1) bf16 "
+                   "register operands, no memory traffic, 60 launches of about 1.5 ms back to back")
+    return out
 
 
 def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
@@ -218,17 +371,10 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     else:
         call = lambda: qjl.qjl_quantize_keys(K, S, bits, norms)
     stream = torch.cuda.current_stream().cuda_stream
-    for _ in range(warmup):
-        call()
-    torch.cuda.synchronize()
-    a, b = ev.create(), ev.create()
-    ev.record(a, stream)
-    for _ in range(steps):
-        call()
-    ev.record(b, stream)
-    ms = ev.elapsed_ms(a, b) / steps          # one kernel per call, back to back: events bracket the kernels
-    ev.destroy(a)
-    ev.destroy(b)
+    # one kernel per call, back to back: events bracket the kernels.  The warm-up is long enough (tens of
+    # milliseconds) for the clocks to settle to what the chip holds under this load: the first hundred launches
+    # after an idle stretch run about 10 % slower than the steady state that follows.
+    ms = timed_launches(ev, stream, lambda i: call(), steps, warmup)
     rows = w.batch * w.kv_heads * w.n
     flops = 2.0 * w.d * mt * rows
     achieved = flops / (ms * 1e-3) / 1e12
@@ -241,6 +387,9 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
         "ms_per_step": ms,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": load_traffic(w.name),
+                     "ceiling": CEIL.get("mfma_TFLOPs"),
+                     "frac_of_ceiling": achieved / CEIL["mfma_TFLOPs"] if CEIL.get("mfma_TFLOPs") else None,
+                     "launches_back_to_back": steps,
                      "kernel": "quantize_slds_kernel" if mt <= 512 else "quantize_mfma_kernel", "kernel_ms": ms, "flops": flops,
                      "algorithmic_bytes": algo_bytes, "hbm_GBs": algo_bytes / (ms * 1e-3) / 1e9},
     }
@@ -341,18 +490,39 @@ def bench_sketches(qjl, ev, dev):
     return out
 
 
-def cpu_baseline(inputs, w, budget_s=12.0):
-    """The oracle, as it stands, on the host cores: the same decode step
-    (project -> scores -> softmax -> values) on the same workload."""
+def _oracle_threads():
+    from threadpoolctl import threadpool_info
+    return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+
+
+def cpu_decode_baseline(qjl, inputs, w, dev, budget_s=10.0, units=None):
+    """The oracle, as it stands, on the host cores: the same decode step (project -> scores -> softmax -> values) on a
+    bounded sample of the workload -- the first batch entry (and, if `units` is given, its first `units` kv heads with
+    their query heads), at the full context length.  The sample's keys are also quantized on the GPU and the two codes
+    compared: the second return value counts the sign decisions that differ (Definition 3.1 with sign(0) = +1; entries
+    with |(S k)_i| < 1e-5 ||s_i|| ||k|| are the near-zero band in which fp32 rounding may decide differently)."""
+    import dataclasses
     import numpy as np
-    from threadpoolctl import threadpool_info, threadpool_limits
+    import torch
+    from threadpoolctl import threadpool_limits
     from oracle import qjl_oracle as orc
-    K, Q, V = inputs.make_workload_tensors(w, "cpu")
+    G = w.q_heads // w.kv_heads
+    kvh = min(units or w.kv_heads, w.kv_heads)
+    ws = dataclasses.replace(w, batch=1, kv_heads=kvh, q_heads=kvh * G)
+    K, Q, V = inputs.make_workload_tensors(ws, "cpu")
     S = orc.gaussian_sketch(w.sketch_seed, w.m, w.d, "bf16")
     K64, Q64, V64 = inputs.to_f64(K), inputs.to_f64(Q), inputs.to_f64(V)
-    bits, nu16, _ = orc.quantize_keys(K64, S)             # untimed, as on the GPU
     cores = min(16, os.cpu_count() or 1)
     with threadpool_limits(limits=cores):
+        bits, nu16, P = orc.quantize_keys(K64, S)             # untimed, as on the GPU
+        S_dev = torch.from_numpy(S).to(dev).to(w.dtype)       # exact: the oracle's sketch is already rounded to bf16
+        gbits, _ = qjl.qjl_quantize_keys(K.to(dev), S_dev)
+        diff = orc.unpack_signs(gbits.cpu().numpy(), w.m) != orc.unpack_signs(bits, w.m)
+        band = np.abs(P) < 1e-5 * np.linalg.norm(S, axis=1) * np.linalg.norm(K64, axis=-1, keepdims=True)
+        signs = {"sample": f"{ws.key_heads} keys x {w.m} projections of {w.name} (batch entry 0, {kvh} kv heads), GPU code against the oracle's",
+                 "entries": int(diff.size), "near_zero_entries": int(band.sum()),
+                 "near_zero_flips": int((diff & band).sum()), "mismatches_outside_band": int((diff & ~band).sum())}
+        del P, diff, band, gbits
         orc.decode_attention(Q64, S, bits, nu16, V64, w.scale)   # warm-up
         reps, t0 = 0, time.perf_counter()
         while True:
@@ -361,23 +531,53 @@ def cpu_baseline(inputs, w, budget_s=12.0):
             el = time.perf_counter() - t0
             if el >= budget_s or reps >= 500:
                 break
-        used = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    return {"value": w.key_heads * reps / el, "unit": "keys/s", "cores": int(min(cores, used)), "kind": "oracle",
-            "sample": f"{reps} full decode steps of {w.name} (all {w.key_heads} keys each), numpy float64, "
-                      f"{el:.1f} s of CPU work"}
+        used = _oracle_threads()
+    base = {"value": ws.key_heads * reps / el, "unit": "keys/s", "cores": int(min(cores, used)), "kind": "oracle",
+            "workload": w.name,
+            "sample": f"{reps} decode steps over batch entry 0 of {w.batch}, {kvh} of {w.kv_heads} kv heads with their "
+                      f"{kvh * G} query heads, full context {w.n} ({ws.key_heads} of {w.key_heads} keys per step), "
+                      f"numpy float64, {el:.1f} s of CPU work"}
+    return base, signs
+
+
+def cpu_quantize_baseline(inputs, w, stride=16, budget_s=10.0):
+    """The oracle's key quantizer (project, sign, pack, norm) on 1/stride of the prefill workload's tokens."""
+    import dataclasses
+    from threadpoolctl import threadpool_limits
+    from oracle import qjl_oracle as orc
+    ws = dataclasses.replace(w, n=w.n // stride)
+    K = inputs.make_keys(ws.batch, ws.kv_heads, ws.n, ws.d, ws.dtype, ws.data_seed, "cpu", ws.outliers)
+    S = orc.gaussian_sketch(w.sketch_seed, w.m, w.d, "bf16")
+    K64 = inputs.to_f64(K)
+    cores = min(16, os.cpu_count() or 1)
+    with threadpool_limits(limits=cores):
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            orc.quantize_keys(K64, S)
+            reps += 1
+            el = time.perf_counter() - t0
+            if el >= budget_s or reps >= 100:
+                break
+        used = _oracle_threads()
+    return {"value": ws.batch * ws.n * reps / el, "unit": "tokens/s", "cores": int(min(cores, used)), "kind": "oracle",
+            "workload": w.name,
+            "sample": f"{reps} passes over {ws.n} of {w.n} tokens per head (1/{stride} of the workload, all {w.kv_heads} heads, "
+                      f"{ws.batch * ws.kv_heads * ws.n} keys per pass), numpy float64, {el:.1f} s of CPU work"}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="c2", help="headline workload: c2 (default, the configuration the "
-                    "metric is quoted on), c3, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="c3", help="headline workload: c3 (default: the largest configuration that one "
+                    "GPU holds), c2, c5a, c5b (decode), c4 (prefill quantize), or c2d / c3d / c4d (the same with the outlier channels "
                     "quantized separately), c2v / c3v / c5bv (decode on a 4-bit value cache; c3v2, c3v8: 2 and 8 bits), c2s (append + decode), for profiling single kernels; "
-                    "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters")
+                    "'copy' runs a plain 1 GiB device copy to calibrate the HBM byte counters; 'ceilings' only the calibration kernels")
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baselines")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming-read and MFMA-loop calibration")
+    ap.add_argument("--cold", action="store_true", help="with --no-extra: also time the headline workload on rotating copies of its cache")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the hot path has no cross-GPU step); "
@@ -397,13 +597,21 @@ def main() -> int:
     if args.workload == "copy":
         # calibration aid for the HBM counters: a plain device copy of known size
         # (1 GiB read + 1 GiB written per launch), nothing of the method
+        C = Ceilings().L
         src = torch.ones((1 << 29,), dtype=torch.bfloat16, device=dev)
         dst = torch.empty_like(src)
+        stream = torch.cuda.current_stream().cuda_stream
         for _ in range(max(1, args.steps)):
-            dst.copy_(src)
+            C.ceil_copy(src.data_ptr(), dst.data_ptr(), src.numel() * 2, 256 * 8, stream)
         torch.cuda.synchronize()
-        print(json.dumps({"workload": "copy", "bytes_read_per_launch": src.numel() * 2,
+        print(json.dumps({"workload": "copy", "kernel": "copy_kernel", "bytes_read_per_launch": src.numel() * 2,
                           "bytes_written_per_launch": src.numel() * 2, "launches": max(1, args.steps)}))
+        return 0
+    if not args.no_ceilings or args.workload == "ceilings":
+        CEIL.update(measure_ceilings(ev, dev, quick=args.no_extra and args.workload != "ceilings"))
+        torch.cuda.empty_cache()
+    if args.workload == "ceilings":
+        print(json.dumps({"workload": "ceilings", "ceilings": CEIL}))
         return 0
     names = {k.split("_")[0]: k for k in inputs.WORKLOADS}
     if args.workload not in names or args.workload == "c1":
@@ -416,7 +624,7 @@ def main() -> int:
         r = {"graph_batch": 0}
     else:
         t = prepare_decode(qjl, inputs, w, dev)
-        r = time_decode(qjl, ev, w, t, args.steps, args.warmup)
+        r = time_decode(qjl, ev, w, t, args.steps, args.warmup, cold=args.cold)
         head = decode_record(w, r)
         del t
     torch.cuda.empty_cache()
@@ -438,31 +646,51 @@ def main() -> int:
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "context": w.n, "d": w.d, "m": w.m, "m_out": w.m_out, "vbits": w.vbits, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
         "roofline": head["roofline"],
+        "ceilings": dict(CEIL) if CEIL else None,
     }
+    for k in ("value_cold", "ms_per_step_cold"):
+        if k in head:
+            line[k] = head[k]
 
     if not args.no_extra:
         extra = []
-        for name, steps, warm in [("c3_long_context_b4_32k", 100, 20), ("c5a_llama3_8b_gqa_b1_128k", 200, 20),
-                                  ("c5b_llama3_8b_gqa_b16_8k", 200, 20), ("c2d_llama2_7b_decode_4k_dual", 400, 40),
-                                  ("c3d_long_context_b4_32k_dual", 100, 20), ("c2v_llama2_7b_decode_4k_v4", 400, 40),
-                                  ("c3v_long_context_b4_32k_v4", 100, 20), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20),
-                                  ("c2s_llama2_7b_decode_step_4k", 400, 40)]:
+        # (workload, steps, warm-up, also on rotating copies of the cache)
+        for name, steps, warm, cold in [("c2_llama2_7b_decode_4k", 2000, 200, True), ("c5a_llama3_8b_gqa_b1_128k", 200, 20, True),
+                                        ("c5b_llama3_8b_gqa_b16_8k", 200, 20, True), ("c3_long_context_b4_32k", 100, 20, False),
+                                        ("c2d_llama2_7b_decode_4k_dual", 400, 40, False),
+                                        ("c3d_long_context_b4_32k_dual", 100, 20, False), ("c2v_llama2_7b_decode_4k_v4", 400, 40, False),
+                                        ("c3v_long_context_b4_32k_v4", 100, 20, False), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20, False),
+                                        ("c2s_llama2_7b_decode_step_4k", 400, 40, False)]:
             wx = inputs.WORKLOADS[name]
+            if wx.name == w.name:
+                continue
             tx = prepare_decode(qjl, inputs, wx, dev)
-            extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm)))
+            extra.append(decode_record(wx, time_decode(qjl, ev, wx, tx, steps, warm, cold=cold)))
             del tx
             torch.cuda.empty_cache()
-        extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
-        extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 50, 5))
+        if not args.workload.startswith("c4"):
+            extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 200, 100))
+        extra.append(bench_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev, 200, 100))
         extra.append(bench_value_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         extra.append(bench_scores(qjl, inputs, ev, inputs.WORKLOADS["c3_long_context_b4_32k"], dev, 100, 10))
         line["setup_kernels"] = bench_sketches(qjl, ev, dev)
         line["other_workloads"] = extra
 
-    if not args.no_cpu and not args.workload.startswith("c4") and not w.m_out and not w.vbits and not w.stream:
-        line["cpu_baseline"] = cpu_baseline(inputs, w)
-    else:
-        line["cpu_baseline"] = None
+    line["cpu_baseline"] = None
+    if not args.no_cpu:
+        plain = lambda x: not x.m_out and not x.vbits and not x.stream
+        if args.workload.startswith("c4") and not w.m_out:
+            line["cpu_baseline"] = cpu_quantize_baseline(inputs, w)
+        elif plain(w):
+            line["cpu_baseline"], line["sign_bits"] = cpu_decode_baseline(qjl, inputs, w, dev)
+        if not args.no_extra:
+            others = []
+            w5, w4 = inputs.WORKLOADS["c5a_llama3_8b_gqa_b1_128k"], inputs.WORKLOADS["c4_prefill_quantize_64k"]
+            if w.name != w5.name:
+                others.append(cpu_decode_baseline(qjl, inputs, w5, dev, budget_s=8.0, units=2)[0])
+            if w.name != w4.name:
+                others.append(cpu_quantize_baseline(inputs, w4, budget_s=8.0))
+            line["cpu_baselines_other"] = others
     print(json.dumps(line))
     return 0
 

@@ -10,6 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqjl.so")
+BENCH_LIB = os.path.join(HERE, "libqjl_ceilings.so")      # calibration kernels of bench.py, not part of the library
+BENCH_SOURCES = ["bench_ceilings.hip"]
 SOURCES = ["qjl_api.hip", "qjl_sketch.hip", "qjl_project.hip", "qjl_quantize.hip",
            "qjl_scores.hip", "qjl_decode.hip", "qjl_outlier.hip", "qjl_values.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -29,7 +31,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
-    for src in SOURCES:
+    for src in SOURCES + BENCH_SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [hipcc(), *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -42,12 +44,13 @@ def build(verbose: bool = True, extra_flags=()) -> str:
         if verbose and lines:
             print("\n".join(lines))
         objs.append(obj)
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stdout)
-    if verbose:
-        print(f"built {LIB}")
+    for lib, group in ((LIB, objs[:len(SOURCES)]), (BENCH_LIB, objs[len(SOURCES):])):
+        cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", lib]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stdout)
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

@@ -1,0 +1,162 @@
+// Calibration kernels for the benchmark: what this chip sustains on the two
+// resources the QJL kernels are bound by, measured the same way as the kernels
+// themselves.  Not part of the library (built into libqjl_ceilings.so, loaded
+// by bench.py only) and nothing of the method is in here.
+//
+//   ceil_stream_read   every byte of a buffer read once with 16-byte loads,
+//                      nothing written: the HBM read rate a streaming kernel
+//                      such as the decode step can reach at that size.
+//   ceil_copy          the same with every 16 bytes written to a second buffer
+//                      (known read and write sizes: calibrates byte counters).
+//   ceil_mfma_loop     back-to-back v_mfma_f32_16x16x32_bf16 / 32x32x16 on
+//                      register operands, eight waves per CU like the key
+//                      quantizer, no memory traffic in the loop: the matrix
+//                      rate the chip sustains at the clock it settles to under
+//                      that load.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kReadUnroll = 8;
+
+template <bool NT> __device__ __forceinline__ u32x4_t ld16(const u32x4_t* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+// NT: loads marked non-temporal.  CHUNKED: a workgroup reads one contiguous piece of the buffer (the way a
+// decode workgroup reads its chunk of the context); otherwise consecutive workgroups read consecutive 4 KB.
+template <bool NT, bool CHUNKED>
+__global__ void __launch_bounds__(256) stream_read_kernel(const u32x4_t* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  size_t i, end, stride;
+  if constexpr (CHUNKED) {
+    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    i = (size_t)blockIdx.x * per + threadIdx.x;
+    end = min(n16, (size_t)(blockIdx.x + 1) * per);
+    stride = 256;
+  } else {
+    i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    end = n16;
+    stride = (size_t)gridDim.x * 256;
+  }
+  u32x4_t acc = {0u, 0u, 0u, 0u};
+  for (; i + (kReadUnroll - 1) * stride < end; i += kReadUnroll * stride) {
+    u32x4_t v[kReadUnroll];
+#pragma unroll
+    for (int u = 0; u < kReadUnroll; ++u) v[u] = ld16<NT>(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < kReadUnroll; ++u) acc ^= v[u];
+  }
+  for (; i < end; i += stride) acc ^= ld16<NT>(src + i);
+  const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+  if (x == 0x9E3779B9u && sink != nullptr) sink[0] = x;   // keeps the loads alive; practically never taken
+}
+
+__global__ void __launch_bounds__(256) copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst,
+                                                   size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Operands: eight 16-byte fragments per lane from `frag` (values chosen by the
+// caller: N(0,1) for the quantizer's operand statistics, zeros for an idle data
+// path).  WIDE = false: 16x16x32 with sixteen accumulator chains of 4 registers
+// (the quantizer's instruction); true: 32x32x16 with four chains of 16.
+template <bool WIDE>
+__global__ void __launch_bounds__(512, 1) mfma_loop_kernel(const u32x4_t* __restrict__ frag, int iters,
+                                                           float* __restrict__ sink) {
+  const int lane = threadIdx.x & 63;
+  bf16x8_t a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    u32x4_t x = frag[(i * 64 + lane)], y = frag[((4 + i) * 64 + lane)];
+    __builtin_memcpy(&a[i], &x, 16);
+    __builtin_memcpy(&b[i], &y, 16);
+  }
+  float total = 0.f;
+  if constexpr (WIDE) {
+    f32x16_t acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s], b[c], acc[c], 0, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) total += acc[c][v];
+  } else {
+    f32x4_t acc[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+          acc[4 * s + c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], b[c], acc[4 * s + c], 0, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) total += acc[c][0] + acc[c][1] + acc[c][2] + acc[c][3];
+  }
+  if (total == 12345.678f && sink != nullptr) sink[0] = total;   // keeps the chains alive
+}
+
+}  // namespace
+
+extern "C" {
+
+// Reads `bytes` (a multiple of 16) from src once.  grid_blocks workgroups of 256 threads.
+// mode bit 0: non-temporal loads; bit 1: one contiguous piece per workgroup.
+int ceil_stream_read(const void* src, size_t bytes, int grid_blocks, int mode, void* sink, void* stream) {
+  if (src == nullptr || bytes == 0 || bytes % 16 != 0 || grid_blocks < 1 || mode < 0 || mode > 3) return -1;
+  const dim3 grid((unsigned)grid_blocks), block(256);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const u32x4_t* p = static_cast<const u32x4_t*>(src);
+  uint32_t* k = static_cast<uint32_t*>(sink);
+  switch (mode) {
+    case 0: hipLaunchKernelGGL((stream_read_kernel<false, false>), grid, block, 0, st, p, bytes / 16, k); break;
+    case 1: hipLaunchKernelGGL((stream_read_kernel<true, false>), grid, block, 0, st, p, bytes / 16, k); break;
+    case 2: hipLaunchKernelGGL((stream_read_kernel<false, true>), grid, block, 0, st, p, bytes / 16, k); break;
+    default: hipLaunchKernelGGL((stream_read_kernel<true, true>), grid, block, 0, st, p, bytes / 16, k); break;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+// Copies `bytes` (a multiple of 16) from src to dst.
+int ceil_copy(const void* src, void* dst, size_t bytes, int grid_blocks, void* stream) {
+  if (src == nullptr || dst == nullptr || bytes == 0 || bytes % 16 != 0 || grid_blocks < 1) return -1;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)grid_blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4_t*>(src), static_cast<u32x4_t*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+// frag: 8 * 64 * 16 bytes of bf16 operands.  One launch = grid_blocks workgroups of eight waves, each wave
+// `iters` * 16 MFMAs.  Returns the floating-point operations of the launch through *flops.
+int ceil_mfma_loop(const void* frag, int wide, int iters, int grid_blocks, void* sink, double* flops, void* stream) {
+  if (frag == nullptr || iters < 1 || grid_blocks < 1) return -1;
+  if (wide)
+    hipLaunchKernelGGL(mfma_loop_kernel<true>, dim3((unsigned)grid_blocks), dim3(512), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const u32x4_t*>(frag), iters,
+                       static_cast<float*>(sink));
+  else
+    hipLaunchKernelGGL(mfma_loop_kernel<false>, dim3((unsigned)grid_blocks), dim3(512), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const u32x4_t*>(frag), iters,
+                       static_cast<float*>(sink));
+  if (flops) *flops = (double)grid_blocks * 8.0 * iters * 16.0 * (wide ? 32768.0 : 16384.0);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+}  // extern "C"
