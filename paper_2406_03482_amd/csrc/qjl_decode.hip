@@ -61,12 +61,21 @@ struct decode_args {
   uint16_t* norms_w;
 };
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// The value cache is read exactly once per call and is far larger than any
+// cache: its loads are marked non-temporal, so that the lines neither stay in
+// L2 nor are written into the 256 MB last-level cache on their way through.
+// (4 x 32 heads x 32768 keys: 199 -> 177 us per step, 0.76 -> 0.86 of 8 TB/s;
+// grouped-query shapes of 304 MB on rotating copies: 0.63 -> 0.70.)
 // 16 bytes of V -> 8 floats (16-bit types) ...
 template <typename T> struct vtile {
   static constexpr int kRegs = 1;  // uint4 per 8 elements
   uint4 r;
   __device__ __forceinline__ void load(const void* V, uint32_t elem) {
-    r = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(V) + elem);
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(static_cast<const uint16_t*>(V) + elem));
+    r = make_uint4(t[0], t[1], t[2], t[3]);
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
     unpack2<T>(r.x, x[0], x[1]); unpack2<T>(r.y, x[2], x[3]);
@@ -77,8 +86,9 @@ template <typename T> struct vtile {
 template <> struct vtile<f32_t> {
   float4 a, b;
   __device__ __forceinline__ void load(const void* V, uint32_t elem) {
-    const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(V) + elem);
-    a = p[0]; b = p[1];
+    const f32x4_t* p = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(V) + elem);
+    const f32x4_t t0 = __builtin_nontemporal_load(p), t1 = __builtin_nontemporal_load(p + 1);
+    a = make_float4(t0[0], t0[1], t0[2], t0[3]); b = make_float4(t1[0], t1[1], t1[2], t1[3]);
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
@@ -91,9 +101,6 @@ template <> struct vtile<f32_t> {
 // their slice of q and add up inside the 16-lane DPP row.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
 template <typename T> struct slice8 {   // eight consecutive elements, as stored
   u32x4_t r;
   __device__ __forceinline__ void load(const void* base, size_t elem) {
@@ -162,7 +169,7 @@ template <int BITS> struct vtile_q;
 template <> struct vtile_q<4> {
   uint32_t r;
   __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
-    r = *reinterpret_cast<const uint32_t*>(static_cast<const char*>(V) + byte_off);
+    r = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(static_cast<const char*>(V) + byte_off));
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
     bytes_to_floats(r & 0x0F0F0F0Fu, (r >> 4) & 0x0F0F0F0Fu, x);
@@ -171,7 +178,7 @@ template <> struct vtile_q<4> {
 template <> struct vtile_q<2> {
   uint32_t r;
   __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
-    r = *reinterpret_cast<const uint16_t*>(static_cast<const char*>(V) + byte_off);
+    r = __builtin_nontemporal_load(reinterpret_cast<const uint16_t*>(static_cast<const char*>(V) + byte_off));
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
     uint32_t t = (r | (r << 8)) & 0x00FF00FFu;      // the two code bytes, a byte apart
@@ -182,7 +189,9 @@ template <> struct vtile_q<2> {
 template <> struct vtile_q<8> {
   uint2 r;
   __device__ __forceinline__ void load(const void* V, uint32_t byte_off) {
-    r = *reinterpret_cast<const uint2*>(static_cast<const char*>(V) + byte_off);
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(static_cast<const char*>(V) + byte_off));
+    r = make_uint2(t[0], t[1]);
   }
   __device__ __forceinline__ void get(float (&x)[8]) const {
     asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(r.x));
