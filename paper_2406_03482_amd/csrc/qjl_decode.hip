@@ -211,7 +211,7 @@ template <> struct vtile_q<8> {
 // every channel, is carried next to the softmax denominator.
 template <typename T, int GT, int MW, int MWB, int VB, bool AP>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes, VB > 0) * 64,
-                                  T::bytes == 4 ? 1 : (decode_waves(GT, MW * 32, 2, VB > 0) == 4 && GT == 1) ? 4 : 2)
+                                  (T::bytes == 4 || GT == 4) ? 1 : (decode_waves(GT, MW * 32, 2, VB > 0) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes, VB > 0);
   constexpr int MWA = MW - MWB;                        // words of the first instance
@@ -256,12 +256,17 @@ decode_kernel(decode_args a) {
 
   // ---- the rows of S and the queries first: loads come back in issue order, and
   // S q (then the tables) is the first thing that has to be ready
-  // LPR lanes share a row of S.  With 16 every lane holds one 8-element slice per
-  // row and a row's sum takes four DPP steps; with 4 a lane holds four slices
+  // LPR = 4 lanes share a row of S: a lane holds four 8-element slices of the row
   // (slices c, c+4, c+8, c+12, so that a quad still reads 64 contiguous bytes)
-  // and two steps finish four times as many rows at once.  The second form
-  // needs four query slices per head in registers: used while GT <= 2.
-  constexpr int LPR = GT <= 2 ? 4 : 16;
+  // and two DPP steps finish the row's sum.  (Sixteen lanes per row with one
+  // slice each and four DPP steps is the same arithmetic in four times as many
+  // dependent reduction steps: with four query heads per workgroup it took 2.5 us
+  // of the prologue, against 0.8 us for one head in this form.)  The four query
+  // slices per head take 16 registers per head; the four-head group has a CU to
+  // itself (its tables fill the LDS), so it may use up to 256 registers.  Only
+  // fp32 slices of four heads (32 bytes each) would not fit: they keep sixteen
+  // lanes per row.
+  constexpr int LPR = (GT == 4 && T::bytes == 4) ? 16 : 4;
   constexpr int SPL = 16 / LPR;                        // slices per lane and row
   constexpr int kRowsPerPass = kNW * 64 / LPR;
   constexpr int kPasses = M / kRowsPerPass;
