@@ -81,6 +81,15 @@ Readings of points the paper leaves open (all restated where they are used):
     give exactly what quantizing all keys at once gives
     (tests/test_oracle_stream_pins.py).
 
+  * The paper's operating point (Section 4.1: "in all experiments" the keys get
+    the outlier/inlier codes; Section 3.2: the values are quantized token-wise;
+    Algorithm 1: both caches grow as the stream arrives): `generation_step` is
+    one iteration with all three at once -- the new token's key gets its
+    two-part code, its value row its few-bit code, both go to row `pos`, and
+    attention over rows 0..pos uses the sum of the two Eq. (4) estimates and
+    the values as stored.  It is a composition of the functions above and
+    nothing else; pinned by tests/test_oracle_operating_point_pins.py.
+
 Array conventions (all dense, C order):
     K, V  [B, Hkv, n, d]     Q   [B, Hq, d]      S      [m, d]
     bits  [B, Hkv, n, m/8]   nu  [B, Hkv, n]     SQ     [B, Hq, m]
@@ -462,3 +471,44 @@ def decode_step(Q, S, bits, nu16, V, K_new, pos: int, scale: float = 1.0) -> np.
     attention runs over rows 0..pos (V must already hold the new token's value in row pos)."""
     append_keys(bits, nu16, K_new, S, pos)
     return decode_attention(Q, S, bits[:, :, :pos + 1], nu16[:, :, :pos + 1], np.asarray(V)[:, :, :pos + 1], scale)
+
+
+# --------------------------------------------------------------------------
+# The paper's operating point: two-part key codes (Section 4.1), few-bit
+# values (Section 3.2) and a cache that grows with the stream (Algorithm 1)
+# --------------------------------------------------------------------------
+def decode_attention_dual_vq(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, vcodes, vscale16, vzero16,
+                             vbits: int = 4, scale: float = 1.0) -> np.ndarray:
+    """One decode step on a cache with two-part key codes and quantized values: the sum of the two Eq. (4)
+    estimates (Section 4.1), softmax, and Eq. (1) on the values as stored (Section 3.2)."""
+    scores = estimate_scores_dual(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, scale)
+    return attention_from_scores(scores, dequantize_values(vcodes, vscale16, vzero16, vbits))
+
+
+def append_token(bits, nu_in16, nu_out16, vcodes, vscale16, vzero16, K_new, V_new, S_in, S_out, channels,
+                 pos: int, vbits: int = 4):
+    """Algorithm 1's loop body without the estimate: the token arriving at position `pos` (K_new, V_new
+    [B,Hkv,1,d]) is quantized -- the key by the two quantizers of Section 4.1, the value row token-wise as in
+    Section 3.2 -- and written to row `pos` of the six cache arrays (modified in place)."""
+    if K_new.shape[2] != 1 or V_new.shape[2] != 1:
+        raise ValueError("one token per step")
+    if pos < 0 or pos >= bits.shape[2]:
+        raise ValueError("append outside the cache")
+    b_new, in_new, out_new, _, _ = quantize_keys_dual(K_new, S_in, S_out, channels)
+    c_new, s_new, z_new = quantize_values(V_new, vbits)
+    bits[:, :, pos] = b_new[:, :, 0]
+    nu_in16[:, :, pos] = in_new[:, :, 0]
+    nu_out16[:, :, pos] = out_new[:, :, 0]
+    vcodes[:, :, pos] = c_new[:, :, 0]
+    vscale16[:, :, pos] = s_new[:, :, 0]
+    vzero16[:, :, pos] = z_new[:, :, 0]
+
+
+def generation_step(Q, S_in, S_out, channels, bits, nu_in16, nu_out16, vcodes, vscale16, vzero16, K_new, V_new,
+                    pos: int, vbits: int = 4, scale: float = 1.0) -> np.ndarray:
+    """One generation step at the paper's operating point: append the new token (key and value) at row `pos`,
+    then attend over rows 0..pos of the caches of capacity bits.shape[2]."""
+    append_token(bits, nu_in16, nu_out16, vcodes, vscale16, vzero16, K_new, V_new, S_in, S_out, channels, pos, vbits)
+    e = pos + 1
+    return decode_attention_dual_vq(Q, S_in, S_out, channels, bits[:, :, :e], nu_in16[:, :, :e], nu_out16[:, :, :e],
+                                    vcodes[:, :, :e], vscale16[:, :, :e], vzero16[:, :, :e], vbits, scale)
