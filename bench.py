@@ -107,12 +107,18 @@ def prepare_decode(qjl, inputs, w, dev):
         ch = qjl.qjl_select_outliers(K, 4)
         S = qjl.qjl_make_dual_sketch(S, S_out, ch)
         bits, norms, norms_out = qjl.qjl_quantize_keys_dual(K, S, ch, w.m_out)
+        k_last = K[:, :, -1:].contiguous() if w.stream else None
         del K
         ws = torch.empty((qjl.qjl_decode_dual_workspace_bytes(w.batch, w.q_heads, w.kv_heads, w.n, w.d, w.m,
                                                               w.m_out, w.dtype),), dtype=torch.uint8, device=dev)
         out = torch.empty((w.batch, w.q_heads, w.d), dtype=torch.float32, device=dev)
+        extra_v = {}
+        if w.vbits:                                 # ... and the values token-wise (Section 3.2): the paper's operating point
+            vc, vs, vz = qjl.qjl_quantize_values(V, w.vbits)
+            extra_v = dict(vcodes=vc, vscale=vs, vzero=vz, v_last=V[:, :, -1:].contiguous() if w.stream else None, ch=ch)
+            V = None
         torch.cuda.synchronize()
-        return dict(Q=Q, S=S, bits=bits, norms=norms, norms_out=norms_out, V=V, ws=ws, out=out)
+        return dict(Q=Q, S=S, bits=bits, norms=norms, norms_out=norms_out, V=V, ws=ws, out=out, k_last=k_last, **extra_v)
     bits, norms = qjl.qjl_quantize_keys(K, S)       # untimed: the cache already exists at decode time
     k_last = K[:, :, -1:].contiguous() if w.stream else None
     del K
@@ -130,6 +136,15 @@ def prepare_decode(qjl, inputs, w, dev):
 
 
 def run_decode(qjl, t, w, events=None):
+    if w.stream and w.m_out and w.vbits:   # the newest token's key and value are quantized into the last row, then attention
+        qjl.qjl_generation_step(t["Q"], t["k_last"], t["v_last"], t["S"], t["ch"], t["bits"], t["norms"], t["norms_out"],
+                                t["vcodes"], t["vscale"], t["vzero"], w.n - 1, w.m_out, w.vbits, w.scale, out=t["out"],
+                                workspace=t["ws"])
+        return
+    if w.m_out and w.vbits:
+        qjl.qjl_decode_attention_dual_vq(t["Q"], t["S"], t["bits"], t["norms"], t["norms_out"], t["vcodes"], t["vscale"],
+                                         t["vzero"], w.m_out, w.vbits, w.scale, out=t["out"], workspace=t["ws"], events=events)
+        return
     if w.stream:        # the newest key is quantized into the last row, then attention over the full cache
         qjl.qjl_decode_step(t["Q"], t["k_last"], t["S"], t["bits"], t["norms"], t["V"], w.n - 1, w.scale,
                             out=t["out"], workspace=t["ws"])
@@ -660,7 +675,10 @@ def main() -> int:
                                         ("c2d_llama2_7b_decode_4k_dual", 400, 40, False),
                                         ("c3d_long_context_b4_32k_dual", 100, 20, False), ("c2v_llama2_7b_decode_4k_v4", 400, 40, False),
                                         ("c3v_long_context_b4_32k_v4", 100, 20, False), ("c5bv_llama3_8b_gqa_b16_8k_v4", 200, 20, False),
-                                        ("c2s_llama2_7b_decode_step_4k", 400, 40, False)]:
+                                        ("c2s_llama2_7b_decode_step_4k", 400, 40, False),
+                                        ("c3o_long_context_b4_32k_dual_v4", 100, 20, False),
+                                        ("c5bo_llama3_8b_gqa_b16_8k_dual_v4", 200, 20, False),
+                                        ("c2o_llama2_7b_generation_step_4k_dual_v4", 400, 40, False)]:
             wx = inputs.WORKLOADS[name]
             if wx.name == w.name:
                 continue

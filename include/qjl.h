@@ -338,6 +338,52 @@ int qjl_decode_step(const qjl_shape* shape, int pos, const void* K_new, const vo
                     uint8_t* bits, uint16_t* norms, const void* V, float* out, void* workspace,
                     size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * The paper's operating point as one path: two-part key codes (Section 4.1,
+ * used "in all experiments"), token-wise quantized values (Section 3.2) and a
+ * cache that grows with the token stream (Algorithm 1).  m + m_out = 384 with
+ * 4-bit values is 3 bits per cached number for the keys and 4.25 for the
+ * values.  Supported: d == 128, m in {128, 256}, m_out == 128, vbits in
+ * {2, 4, 8}, 16-bit shape->dtype.
+ * ---------------------------------------------------------------------- */
+
+/*
+ * qjl_decode_attention_dual with the values taken from a cache written by
+ * qjl_quantize_values:
+ *   out[B,Hq,d] <- sum_j softmax_j(score_j) * (vzero[j] + vscale[j] * code[j,:])
+ * with score_j the sum of the two Eq. (4) estimates as in
+ * qjl_decode_attention_dual.  Workspace: qjl_decode_dual_workspace_bytes(shape,
+ * m_out); events as in qjl_decode_attention_timed.
+ */
+int qjl_decode_attention_dual_vq(const qjl_shape* shape, int m_out, int vbits, const void* Q,
+                                 const void* S_dual, const uint8_t* bits, const uint16_t* norms_in,
+                                 const uint16_t* norms_out, const uint8_t* vcodes,
+                                 const uint16_t* vscale, const uint16_t* vzero, float* out,
+                                 void* workspace, size_t workspace_bytes, void* stream,
+                                 void* event_before, void* event_after);
+
+/*
+ * One generation step (the body of Algorithm 1's loop) on such caches of
+ * capacity shape->n rows per (batch, kv head).  The new token's key
+ * K_new[B,Hkv,1,d] is quantized by the two quantizers of Section 4.1 --
+ * sign(S_dual k) and the norms of k without / on its head's outlier channels
+ * (channels[B,Hkv,count], as in qjl_quantize_keys_dual) -- and its value row
+ * V_new[B,Hkv,1,d] token-wise as in qjl_quantize_values; both are written to row
+ * `pos` of bits / norms_in / norms_out / vcodes / vscale / vzero.  Then
+ *   out[B,Hq,d] <- attention of Q[B,Hq,d] over rows 0..pos,
+ * the new token included with its code and its value as stored.  One launch of
+ * the attention kernel (+ the chunk merge): the new row is quantized inside it,
+ * used from on-chip memory, and written to the caches by that kernel; it is
+ * complete when the call's work on `stream` is.  0 <= pos < shape->n.
+ * Workspace: qjl_decode_dual_workspace_bytes(shape, m_out), taken at the
+ * capacity, covers every pos.
+ */
+int qjl_generation_step(const qjl_shape* shape, int m_out, int vbits, int pos, const void* K_new,
+                        const void* V_new, const void* Q, const void* S_dual,
+                        const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                        uint16_t* norms_out, uint8_t* vcodes, uint16_t* vscale, uint16_t* vzero,
+                        float* out, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

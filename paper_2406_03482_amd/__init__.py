@@ -10,10 +10,12 @@ from .binding import (QJLShape, QJLError, lib, lib_path, qjl_make_sketch, qjl_ma
                       qjl_decode_attention, qjl_decode_plan, qjl_decode_attention_noalloc, qjl_select_outliers, qjl_make_dual_sketch,
                       qjl_quantize_keys_dual, qjl_decode_dual_workspace_bytes,
                       qjl_decode_attention_dual, qjl_quantize_values, qjl_decode_attention_vq, qjl_append_keys, qjl_decode_step,
+                      qjl_decode_attention_dual_vq, qjl_generation_step,
                       QJL_F32, QJL_F16, QJL_BF16)
 
 __all__ = ["QJLShape", "QJLError", "lib", "lib_path", "qjl_make_sketch", "qjl_make_sketch_orthogonal", "qjl_quantize_keys",
            "qjl_project_query", "qjl_scores", "qjl_decode_workspace_bytes",
            "qjl_decode_attention", "qjl_decode_plan", "qjl_decode_attention_noalloc", "qjl_select_outliers", "qjl_make_dual_sketch",
            "qjl_quantize_keys_dual", "qjl_decode_dual_workspace_bytes", "qjl_decode_attention_dual",
-           "qjl_quantize_values", "qjl_decode_attention_vq", "qjl_append_keys", "qjl_decode_step", "QJL_F32", "QJL_F16", "QJL_BF16"]
+           "qjl_quantize_values", "qjl_decode_attention_vq", "qjl_append_keys", "qjl_decode_step",
+           "qjl_decode_attention_dual_vq", "qjl_generation_step", "QJL_F32", "QJL_F16", "QJL_BF16"]

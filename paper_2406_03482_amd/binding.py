@@ -90,6 +90,10 @@ def lib() -> ctypes.CDLL:
     L.qjl_quantize_values.argtypes = [sp, ip, vp, vp, vp, vp, vp]
     L.qjl_decode_attention_vq.restype = ctypes.c_int
     L.qjl_decode_attention_vq.argtypes = [sp, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    L.qjl_decode_attention_dual_vq.restype = ctypes.c_int
+    L.qjl_decode_attention_dual_vq.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+    L.qjl_generation_step.restype = ctypes.c_int
+    L.qjl_generation_step.argtypes = [sp, ip, ip, ip, vp, vp, vp, vp, vp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.qjl_append_keys.restype = ctypes.c_int
     L.qjl_append_keys.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp]
     L.qjl_decode_step.restype = ctypes.c_int
@@ -450,4 +454,78 @@ def qjl_decode_step(Q: torch.Tensor, K_new: torch.Tensor, S: torch.Tensor, bits:
                                  _dev(bits, "bits"), _dev(norms, "norms"), _dev(V, "V"), _dev(out, "out"),
                                  _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                  _stream(Q)))
+    return out
+
+
+# ---- the paper's operating point: two-part key codes + quantized values (+ the stream)
+def qjl_decode_attention_dual_vq(Q: torch.Tensor, S_dual: torch.Tensor, bits: torch.Tensor, norms_in: torch.Tensor,
+                                 norms_out: torch.Tensor, vcodes: torch.Tensor, vscale: torch.Tensor,
+                                 vzero: torch.Tensor, m_out: int, vbits: int = 4, scale: float = 1.0,
+                                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                                 events: Optional[Tuple[int, int]] = None) -> torch.Tensor:
+    """One decode step on two-part key codes and quantized values -> float32 [B,Hq,d]."""
+    B, Hq, d = Q.shape
+    _, Hkv, n, vb = vcodes.shape
+    mt = S_dual.shape[2]
+    m = mt - m_out
+    if S_dual.dtype != Q.dtype or vb * 8 != d * vbits or tuple(S_dual.shape) != (B, Hkv, mt, d):
+        raise ValueError("S_dual must be [B,Hkv,m+m_out,d] with the dtype of Q; vcodes [B,Hkv,n,d*vbits/8]")
+    if tuple(bits.shape) != (B, Hkv, n, mt // 8):
+        raise ValueError("bits do not match the value cache and S_dual")
+    for t in (norms_in, norms_out, vscale, vzero):
+        if tuple(t.shape) != (B, Hkv, n):
+            raise ValueError("norms / vscale / vzero must be [B,Hkv,n]")
+    need = qjl_decode_dual_workspace_bytes(B, Hq, Hkv, n, d, m, m_out, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, n, d, m, _tag(Q), scale)
+    _check("qjl_decode_attention_dual_vq",
+           lib().qjl_decode_attention_dual_vq(ctypes.byref(sh), m_out, vbits, _dev(Q, "Q"), _dev(S_dual, "S_dual"),
+                                              _dev(bits, "bits"), _dev(norms_in, "norms_in"),
+                                              _dev(norms_out, "norms_out"), _dev(vcodes, "vcodes"),
+                                              _dev(vscale, "vscale"), _dev(vzero, "vzero"), _dev(out, "out"),
+                                              _dev(workspace, "workspace"),
+                                              workspace.numel() * workspace.element_size(), _stream(Q),
+                                              events[0] if events else None, events[1] if events else None))
+    return out
+
+
+def qjl_generation_step(Q: torch.Tensor, K_new: torch.Tensor, V_new: torch.Tensor, S_dual: torch.Tensor,
+                        channels: torch.Tensor, bits: torch.Tensor, norms_in: torch.Tensor, norms_out: torch.Tensor,
+                        vcodes: torch.Tensor, vscale: torch.Tensor, vzero: torch.Tensor, pos: int, m_out: int,
+                        vbits: int = 4, scale: float = 1.0, out: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Append the new token (K_new, V_new [B,Hkv,1,d]) at row pos of the six cache arrays, then attention of
+    Q[B,Hq,d] over rows 0..pos -> float32 [B,Hq,d]."""
+    B, Hq, d = Q.shape
+    _, Hkv, cap, vb = vcodes.shape
+    mt = S_dual.shape[2]
+    m = mt - m_out
+    count = channels.shape[2]
+    if tuple(K_new.shape) != (B, Hkv, 1, d) or tuple(V_new.shape) != (B, Hkv, 1, d) or K_new.dtype != Q.dtype or \
+            V_new.dtype != Q.dtype:
+        raise ValueError("K_new and V_new must be [B,Hkv,1,d] with the dtype of Q")
+    if S_dual.dtype != Q.dtype or vb * 8 != d * vbits or tuple(S_dual.shape) != (B, Hkv, mt, d):
+        raise ValueError("S_dual must be [B,Hkv,m+m_out,d] with the dtype of Q; vcodes [B,Hkv,cap,d*vbits/8]")
+    if tuple(bits.shape) != (B, Hkv, cap, mt // 8) or tuple(channels.shape) != (B, Hkv, count) or \
+            channels.dtype != torch.int32:
+        raise ValueError("bits [B,Hkv,cap,(m+m_out)/8]; channels int32 [B,Hkv,count]")
+    for t in (norms_in, norms_out, vscale, vzero):
+        if tuple(t.shape) != (B, Hkv, cap):
+            raise ValueError("norms / vscale / vzero must be [B,Hkv,cap]")
+    need = qjl_decode_dual_workspace_bytes(B, Hq, Hkv, cap, d, m, m_out, Q.dtype)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
+    sh = _shape(B, Hq, Hkv, cap, d, m, _tag(Q), scale)
+    _check("qjl_generation_step",
+           lib().qjl_generation_step(ctypes.byref(sh), m_out, vbits, pos, _dev(K_new, "K_new"), _dev(V_new, "V_new"),
+                                     _dev(Q, "Q"), _dev(S_dual, "S_dual"), _dev(channels, "channels"), count,
+                                     _dev(bits, "bits"), _dev(norms_in, "norms_in"), _dev(norms_out, "norms_out"),
+                                     _dev(vcodes, "vcodes"), _dev(vscale, "vscale"), _dev(vzero, "vzero"),
+                                     _dev(out, "out"), _dev(workspace, "workspace"),
+                                     workspace.numel() * workspace.element_size(), _stream(Q)))
     return out

@@ -165,11 +165,22 @@ struct decode_plan {
 // holds one stacked sketch [sh.m + m_out, d] per (batch, kv head).  vscale != nullptr: V holds
 // vbits-bit value codes (2, 4 or 8) with a binary16 scale and zero point per token.
 bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_splits = 0);
+// What a generation step on two-part codes and quantized values needs beyond K_new / bits_w / norms_w:
+// where the outlier part's norm and the new token's value row go, and the head's outlier channels.
+struct decode_new_token {
+  uint16_t* norms_out_w;
+  const int32_t* channels;   // [B,Hkv,count]
+  int count;
+  const void* V_new;         // [B,Hkv,1,d]
+  uint8_t* vcodes_w;
+  uint16_t* vscale_w;
+  uint16_t* vzero_w;
+};
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
                   const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after, const void* K_new = nullptr,
-                  uint8_t* bits_w = nullptr, uint16_t* norms_w = nullptr);
+                  uint8_t* bits_w = nullptr, uint16_t* norms_w = nullptr, const decode_new_token* nt = nullptr);
 // K_new != nullptr (16-bit types, m_out = 0, no value codes): K_new[B,Hkv,1,d] is the key of position sh.n - 1;
 // it is quantized inside the attention kernel, attended to, and written to row sh.n - 1 of bits_w / norms_w
 // (the same arrays as bits / norms).

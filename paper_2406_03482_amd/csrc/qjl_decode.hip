@@ -12,6 +12,7 @@
 // the usual max/sum-of-exponentials rescaling.
 #include "qjl_common.hpp"
 #include "qjl_lut.hpp"
+#include "qjl_value_codes.hpp"
 
 #include <hip/hip_ext.h>
 #include <atomic>
@@ -59,6 +60,14 @@ struct decode_args {
   const void* Knew;       // [B,Hkv,1,128], or null
   uint32_t* bits_w;       // the caches again, writable: row n - 1 is written by this call
   uint16_t* norms_w;
+  uint16_t* norms2_w;     // two-part codes: the outlier part's norm
+  const int32_t* channels;// two-part codes: [B,Hkv,count] outlier channels, to split the new key's norm
+  int count;
+  // ... and, with quantized values, so does its value row, which is quantized into row n - 1 as well
+  const void* Vnew;       // [B,Hkv,1,128] (type T), or null
+  uint8_t* vcodes_w;      // the value caches, writable
+  uint16_t* vscale_w;
+  uint16_t* vzero_w;
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -106,12 +115,19 @@ template <typename T> struct slice8 {   // eight consecutive elements, as stored
   __device__ __forceinline__ void load(const void* base, size_t elem) {
     r = *reinterpret_cast<const u32x4_t*>(static_cast<const uint16_t*>(base) + elem);
   }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    unpack2<T>(r[0], x[0], x[1]); unpack2<T>(r[1], x[2], x[3]);
+    unpack2<T>(r[2], x[4], x[5]); unpack2<T>(r[3], x[6], x[7]);
+  }
 };
 template <> struct slice8<f32_t> {
   f32x4_t a, b;
   __device__ __forceinline__ void load(const void* base, size_t elem) {
     const f32x4_t* p = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(base) + elem);
     a = p[0]; b = p[1];
+  }
+  __device__ __forceinline__ void get(float (&x)[8]) const {
+    x[0] = a[0]; x[1] = a[1]; x[2] = a[2]; x[3] = a[3]; x[4] = b[0]; x[5] = b[1]; x[6] = b[2]; x[7] = b[3];
   }
 };
 __device__ __forceinline__ float dot8(const slice8<bf16_t>& s, const slice8<bf16_t>& q) {
@@ -226,8 +242,12 @@ decode_kernel(decode_args a) {
   // byte tables after the last key has been scored.
   // AP: the projections of the new key (M floats), its squared norm, then its
   // code words and its norm as stored -- behind everything else
+  // (two-part codes: two squared norms and two stored norms; quantized values: the
+  // new value row's codes as floats, its scale and zero point, its packed codes)
   float* sk = lut + 32 * M * GT;
-  uint32_t* newcode = reinterpret_cast<uint32_t*>(sk + M + 1);
+  uint32_t* newcode = reinterpret_cast<uint32_t*>(sk + M + 2);
+  float* newval = reinterpret_cast<float*>(newcode + MW + 2);   // [128] codes, then scale and zero point (binary16 bits), then 16 * VB bytes
+  uint32_t* newval_u = reinterpret_cast<uint32_t*>(newval + kD);
   float* pbuf_all = nib;                              // [kNW][64*GT]
   float* merge = lut;                                 // [kNW][GT][132]
   static_assert(kNW * 64 <= 4 * M, "probability buffers must fit the 4-bit tables");
@@ -273,6 +293,8 @@ decode_kernel(decode_args a) {
   static_assert(M % kRowsPerPass == 0, "whole passes over S");
   slice8<T> qs[GT][SPL], srow[kPasses][SPL];
   slice8<T> ks[SPL];                                  // AP: this lane's slices of the new key
+  float vnew[8];                                      // AP with quantized values: entries 8c .. 8c+7 of the new value row
+  constexpr bool APV = AP && VB > 0;
   // AP: the new key is row n - 1; the workgroups whose chunk holds that row
   // quantize it themselves (same S, same walk as for the queries), use its code
   // from LDS and, the first group of query heads only, write it to the caches.
@@ -288,6 +310,7 @@ decode_kernel(decode_args a) {
 #pragma unroll
       for (int i = 0; i < SPL; ++i) ks[i].load(a.Knew, (size_t)bk * kD + (c16 + LPR * i) * 8);
     }
+    if constexpr (APV) load8<T>(a.Vnew, (size_t)bk * kD + (lane & 15) * 8, vnew);
     const size_t s0 = (size_t)bk * a.s_head_stride;
 #pragma unroll
     for (int u = 0; u < kPasses; ++u)
@@ -372,8 +395,38 @@ decode_kernel(decode_args a) {
       }
     }
     if constexpr (AP) {
-      const float kk = row_dot(ks, ks);
-      if (tid == 0) sk[M] = kk;
+      if constexpr (MWB > 0) {
+        // Section 4.1: the inlier code goes with the norm of the key without its head's outlier channels, the
+        // outlier code with the norm of those channels (out-of-range entries ignored, repeats count once)
+        uint32_t cm[4] = {0u, 0u, 0u, 0u};
+        for (int t = 0; t < a.count; ++t) {
+          const int ch = a.channels[(size_t)bk * a.count + t];
+          if (ch >= 0 && ch < kD) cm[ch >> 5] |= 1u << (ch & 31);
+        }
+        float kin = 0.f, kout = 0.f;
+#pragma unroll
+        for (int i = 0; i < SPL; ++i) {
+          const int e0 = (c16 + LPR * i) * 8;            // first element of this slice
+          const uint32_t mb = (cm[e0 >> 5] >> (e0 & 31)) & 0xFFu;
+          float x[8];
+          ks[i].get(x);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const bool o = (mb >> e) & 1u;
+            kout = fmaf(x[e], o ? x[e] : 0.f, kout);
+            kin = fmaf(x[e], o ? 0.f : x[e], kin);
+          }
+        }
+        if constexpr (LPR == 16) { kin = row16_sum(kin); kout = row16_sum(kout); }
+        else {
+          kin += QJL_DPP_F(kin, 0xB1); kin += QJL_DPP_F(kin, 0x4E);
+          kout += QJL_DPP_F(kout, 0xB1); kout += QJL_DPP_F(kout, 0x4E);
+        }
+        if (tid == 0) { sk[M] = kin; sk[M + 1] = kout; }
+      } else {
+        const float kk = row_dot(ks, ks);
+        if (tid == 0) sk[M] = kk;
+      }
     }
   }
   __syncthreads();
@@ -388,7 +441,36 @@ decode_kernel(decode_args a) {
           newcode[i >> 5] = word;
         }
       }
-      if (tid == 0) newcode[MW] = float_to_f16_bits(sqrtf(sk[M]));
+      if (tid == 0) {
+        newcode[MW] = float_to_f16_bits(sqrtf(sk[M]));
+        if constexpr (MWB > 0) newcode[MW + 1] = float_to_f16_bits(sqrtf(sk[M + 1]));
+      }
+      if constexpr (APV) {
+        // Section 3.2 for the new token's value row: the same arithmetic as the bulk quantizer, by the first
+        // sixteen lanes; the codes stay in LDS for this step's own use and go to the cache at the end
+        if (tid < 16) {
+          float lo = vnew[0], hi = vnew[0];
+#pragma unroll
+          for (int e = 1; e < 8; ++e) { lo = fminf(lo, vnew[e]); hi = fmaxf(hi, vnew[e]); }
+          lo = row16_min(lo);
+          hi = row16_max(hi);
+          uint16_t s16, z16;
+          uint32_t q8[8];
+          value_codes8<VB>(vnew, lo, hi, s16, z16, q8);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) newval[tid * 8 + e] = (float)q8[e];
+          if (tid == 0) { newval_u[0] = s16; newval_u[1] = z16; }
+          if constexpr (VB == 8) {
+            newval_u[2 + 2 * tid] = q8[0] | (q8[1] << 8) | (q8[2] << 16) | (q8[3] << 24);
+            newval_u[3 + 2 * tid] = q8[4] | (q8[5] << 8) | (q8[6] << 16) | (q8[7] << 24);
+          } else {
+            uint32_t word = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) word |= q8[e] << (VB * e);
+            newval_u[2 + tid] = word;                   // VB == 2: the low 16 bits
+          }
+        }
+      }
     }
   }
   build_lut<GT>(sq, nib, lut, M, tid, kNW * 64);
@@ -414,12 +496,18 @@ decode_kernel(decode_args a) {
   for (; k0 < k_end; k0 += kNW * 64) {
     const int kn = k0 + kNW * 64;
     const bool have_next = kn < k_end;
+    int new_pass = -1, new_r = 0;                     // APV: the row pass and row group of the new token in this block
+    if constexpr (APV) {
+      if (has_new && pos >= k0 && pos < k0 + 64) { new_pass = (pos - k0) >> 2; new_r = (pos - k0) & 3; }
+    }
     if constexpr (AP) {                               // the lane of the new key takes its code from LDS
       if (has_new && pos >= k0 && pos < k0 + 64) {    // uniform
         if (k0 + lane == pos) {
 #pragma unroll
           for (int w = 0; w < MW; ++w) wcur[w] = newcode[w];
           ncur = (uint16_t)newcode[MW];
+          if constexpr (MWB > 0) ncur2 = (uint16_t)newcode[MW + 1];
+          if constexpr (APV) { vscur = (uint16_t)newval_u[0]; vzcur = (uint16_t)newval_u[1]; }
         }
       }
     }
@@ -478,6 +566,12 @@ decode_kernel(decode_args a) {
       if (i + 1 < 16) pv_next = pw[i + 1];            // hide the LDS latency behind this row's FMAs
       float x[8];
       v[i % VD].get(x);
+      if constexpr (APV) {                              // the new token's row: its codes are in LDS, not yet in the cache
+        if (new_pass == i) {                            // uniform; -1 in every block but the one that holds row pos
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = (lane >> 4) == new_r ? newval[c * 8 + e] : x[e];
+        }
+      }
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] += pv * x[e];
       // The refill overwrites the registers just read.  Tie its address (through r)
@@ -547,6 +641,16 @@ decode_kernel(decode_args a) {
     if (has_new && blockIdx.y == 0) {
       if (tid < MW) a.bits_w[(row0 + pos) * MW + tid] = newcode[tid];
       if (tid == 0) a.norms_w[row0 + pos] = (uint16_t)newcode[MW];
+      if constexpr (MWB > 0) { if (tid == 0) a.norms2_w[row0 + pos] = (uint16_t)newcode[MW + 1]; }
+      if constexpr (APV) {
+        uint8_t* dst = a.vcodes_w + (row0 + pos) * (size_t)(16 * VB);
+        if (tid < 16) {
+          if constexpr (VB == 8) *reinterpret_cast<uint2*>(dst + 8 * tid) = make_uint2(newval_u[2 + 2 * tid], newval_u[3 + 2 * tid]);
+          else if constexpr (VB == 4) *reinterpret_cast<uint32_t*>(dst + 4 * tid) = newval_u[2 + tid];
+          else *reinterpret_cast<uint16_t*>(dst + 2 * tid) = (uint16_t)newval_u[2 + tid];
+        }
+        if (tid == 0) { a.vscale_w[row0 + pos] = (uint16_t)newval_u[0]; a.vzero_w[row0 + pos] = (uint16_t)newval_u[1]; }
+      }
     }
   }
 }
@@ -607,7 +711,10 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
              hipEvent_t ev0, hipEvent_t ev1) {
   static std::atomic<uint64_t> lds_set{0};             // per kernel instantiation: devices whose limit is raised
   constexpr int kNW = decode_waves(GT, MW * 32, T::bytes, VB > 0);
-  const size_t lds = decode_lds_bytes(GT, MW * 32) + (AP ? (MW * 32 + MW + 8) * sizeof(float) : 0);
+  // AP: projections of the new key + two squared norms, its code + two norms, then (quantized values) the new
+  // value row: 128 codes as floats, scale, zero point, up to 128 packed bytes
+  const size_t lds = decode_lds_bytes(GT, MW * 32) +
+                     (AP ? (MW * 32 + 2 + MW + 2 + (VB > 0 ? kD + 2 + 32 : 0) + 2) * sizeof(float) : 0);
   int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP>), lds, lds_set);
   if (rc_lds != QJL_OK) return rc_lds;
   const long pairs = (long)sh.batch * sh.kv_heads;
@@ -631,52 +738,56 @@ int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a,
   }
 }
 
+// The instantiations that exist for a code of MW words whose last MWB belong to a second quantizer:
+//   one-part codes: plain, streaming (AP), quantized values (2, 4, 8 bits)
+//   two-part codes: plain, quantized values, quantized values + streaming (the generation step at the
+//   paper's operating point)
+// Quantized values and streaming take 16-bit queries and sketches.
+template <typename T, int MW, int MWB>
+int launch_v(const qjl_shape& sh, int vbits, bool ap, const decode_plan& plan, const decode_args& a, hipStream_t st,
+             hipEvent_t ev0, hipEvent_t ev1) {
+  if (vbits == 0 && !ap) return launch_g<T, MW, MWB>(sh, plan, a, st, ev0, ev1);
+  if constexpr (T::bytes == 2) {
+    if (vbits == 0) {                                 // streaming on unquantized values: one-part codes
+      if constexpr (MWB == 0) return launch_g<T, MW, 0, 0, true>(sh, plan, a, st, ev0, ev1);
+      else return QJL_ERR_UNSUPPORTED;
+    }
+    if (!ap) {
+      switch (vbits) {
+        case 2: return launch_g<T, MW, MWB, 2>(sh, plan, a, st, ev0, ev1);
+        case 4: return launch_g<T, MW, MWB, 4>(sh, plan, a, st, ev0, ev1);
+        case 8: return launch_g<T, MW, MWB, 8>(sh, plan, a, st, ev0, ev1);
+        default: return QJL_ERR_UNSUPPORTED;
+      }
+    }
+    if constexpr (MWB > 0) {                          // streaming into quantized values: two-part codes
+      switch (vbits) {
+        case 2: return launch_g<T, MW, MWB, 2, true>(sh, plan, a, st, ev0, ev1);
+        case 4: return launch_g<T, MW, MWB, 4, true>(sh, plan, a, st, ev0, ev1);
+        case 8: return launch_g<T, MW, MWB, 8, true>(sh, plan, a, st, ev0, ev1);
+        default: return QJL_ERR_UNSUPPORTED;
+      }
+    }
+  }
+  return QJL_ERR_UNSUPPORTED;
+}
+
 // m = bits of the (first) code part, m_out = bits of the second part (0: none)
 template <typename T>
 int launch_m(const qjl_shape& sh, int m_out, int vbits, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
-  if (a.vscale != nullptr) {                        // quantized values: 16-bit queries, one-part codes
-    if constexpr (T::bytes == 2) {
-      if (m_out != 0) return QJL_ERR_UNSUPPORTED;
-      switch (sh.m * 16 + vbits) {
-        case 128 * 16 + 2: return launch_g<T, 4, 0, 2>(sh, plan, a, st, ev0, ev1);
-        case 128 * 16 + 4: return launch_g<T, 4, 0, 4>(sh, plan, a, st, ev0, ev1);
-        case 128 * 16 + 8: return launch_g<T, 4, 0, 8>(sh, plan, a, st, ev0, ev1);
-        case 256 * 16 + 2: return launch_g<T, 8, 0, 2>(sh, plan, a, st, ev0, ev1);
-        case 256 * 16 + 4: return launch_g<T, 8, 0, 4>(sh, plan, a, st, ev0, ev1);
-        case 256 * 16 + 8: return launch_g<T, 8, 0, 8>(sh, plan, a, st, ev0, ev1);
-        case 512 * 16 + 2: return launch_g<T, 16, 0, 2>(sh, plan, a, st, ev0, ev1);
-        case 512 * 16 + 4: return launch_g<T, 16, 0, 4>(sh, plan, a, st, ev0, ev1);
-        case 512 * 16 + 8: return launch_g<T, 16, 0, 8>(sh, plan, a, st, ev0, ev1);
-        default: return QJL_ERR_UNSUPPORTED;
-      }
-    } else {
-      return QJL_ERR_UNSUPPORTED;
-    }
-  }
-  if (a.Knew != nullptr) {                          // streaming: 16-bit types, one-part codes, unquantized values
-    if constexpr (T::bytes == 2) {
-      if (m_out != 0) return QJL_ERR_UNSUPPORTED;
-      switch (sh.m) {
-        case 128: return launch_g<T, 4, 0, 0, true>(sh, plan, a, st, ev0, ev1);
-        case 256: return launch_g<T, 8, 0, 0, true>(sh, plan, a, st, ev0, ev1);
-        case 512: return launch_g<T, 16, 0, 0, true>(sh, plan, a, st, ev0, ev1);
-        default: return QJL_ERR_UNSUPPORTED;
-      }
-    } else {
-      return QJL_ERR_UNSUPPORTED;
-    }
-  }
+  const bool ap = a.Knew != nullptr;
+  if (a.vscale == nullptr) vbits = 0;
   if (m_out == 0) {
     switch (sh.m) {
-      case 128: return launch_g<T, 4, 0>(sh, plan, a, st, ev0, ev1);
-      case 256: return launch_g<T, 8, 0>(sh, plan, a, st, ev0, ev1);
-      case 512: return launch_g<T, 16, 0>(sh, plan, a, st, ev0, ev1);
+      case 128: return launch_v<T, 4, 0>(sh, vbits, ap, plan, a, st, ev0, ev1);
+      case 256: return launch_v<T, 8, 0>(sh, vbits, ap, plan, a, st, ev0, ev1);
+      case 512: return launch_v<T, 16, 0>(sh, vbits, ap, plan, a, st, ev0, ev1);
       default: return QJL_ERR_UNSUPPORTED;
     }
   }
-  if (m_out == 128 && sh.m == 128) return launch_g<T, 8, 4>(sh, plan, a, st, ev0, ev1);
-  if (m_out == 128 && sh.m == 256) return launch_g<T, 12, 4>(sh, plan, a, st, ev0, ev1);
+  if (m_out == 128 && sh.m == 128) return launch_v<T, 8, 4>(sh, vbits, ap, plan, a, st, ev0, ev1);
+  if (m_out == 128 && sh.m == 256) return launch_v<T, 12, 4>(sh, vbits, ap, plan, a, st, ev0, ev1);
   return QJL_ERR_UNSUPPORTED;
 }
 
@@ -780,7 +891,7 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,
                   const uint16_t* vscale, const uint16_t* vzero, int vbits, long n_cap, float* out, void* workspace,
                   hipStream_t st, hipEvent_t ev_before, hipEvent_t ev_after, const void* K_new, uint8_t* bits_w,
-                  uint16_t* norms_w) {
+                  uint16_t* norms_w, const decode_new_token* nt) {
   char* ws = static_cast<char*>(workspace);
   int rc = QJL_OK;
   decode_args a;
@@ -788,6 +899,13 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.norms2 = norms_out;
   a.vscale = vscale; a.vzero = vzero;
   a.Knew = K_new; a.bits_w = reinterpret_cast<uint32_t*>(bits_w); a.norms_w = norms_w;
+  a.norms2_w = nt ? nt->norms_out_w : nullptr;
+  a.channels = nt ? nt->channels : nullptr;
+  a.count = nt ? nt->count : 0;
+  a.Vnew = nt ? nt->V_new : nullptr;
+  a.vcodes_w = nt ? nt->vcodes_w : nullptr;
+  a.vscale_w = nt ? nt->vscale_w : nullptr;
+  a.vzero_w = nt ? nt->vzero_w : nullptr;
   a.s_head_stride = m_out > 0 ? (size_t)(sh.m + m_out) * kD : 0;
   a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);

@@ -10,6 +10,7 @@
 // are IEEE float32 operations in exactly this order (the kernel takes a shortcut
 // only where it provably gives the same integer).
 #include "qjl_common.hpp"
+#include "qjl_value_codes.hpp"
 
 namespace qjl {
 namespace {
@@ -21,7 +22,6 @@ template <typename T, int BITS>
 __global__ void __launch_bounds__(256)
 value_quant_kernel(const void* __restrict__ V, uint8_t* __restrict__ codes,
                    uint16_t* __restrict__ vscale, uint16_t* __restrict__ vzero, long rows) {
-  constexpr float kLevels = (float)((1 << BITS) - 1);
   const int c = threadIdx.x & 15, r = threadIdx.x >> 4;
   for (long row = (long)blockIdx.x * 16 + r; row < rows; row += (long)gridDim.x * 16) {
     float x[8];
@@ -31,27 +31,9 @@ value_quant_kernel(const void* __restrict__ V, uint8_t* __restrict__ codes,
     for (int e = 1; e < 8; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
     lo = row16_min(lo);
     hi = row16_max(hi);
-    const uint16_t s16 = float_to_f16_bits((hi - lo) / kLevels);
-    const uint16_t z16 = float_to_f16_bits(lo);
-    const float sc = f16_bits_to_float(s16), z = f16_bits_to_float(z16);
-    uint32_t q8[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-    if (sc > 0.f) {
-      // rint((x - z) / sc) without a division per entry: q0 = rint((x - z) * (1/sc)) is accepted when the
-      // remainder (x - z) - q0 * sc (one fused multiply-add: exact up to 2^-25 of a step) is clear of half
-      // a step by a margin.  Then the true quotient lies within 0.5 - margin of q0, and so does its float32
-      // rounding, which is off by at most |quotient| * 2^-24: below 2^-19 for the quotients up to 16.5
-      // that can still round to a code below the clip (b <= 4), below 2^-15 up to 256.5 (b = 8).  Entries
-      // near a tie take the division itself, so every code is the one the definition gives.
-      const float inv = 1.0f / sc;
-      const float clear = (0.5f - (BITS == 8 ? 0x1.0p-14f : 0x1.0p-18f)) * sc;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {                  // a branch per entry: exact ties are common enough with
-        const float t = x[e] - z;                    // 8- to 11-bit inputs that one branch for all eight
-        float q = rintf(t * inv);                    // would send most waves through eight divisions
-        if (!(fabsf(fmaf(-q, sc, t)) < clear)) q = rintf(t / sc);
-        q8[e] = (uint32_t)__builtin_amdgcn_fmed3f(q, 0.f, kLevels);
-      }
-    }
+    uint16_t s16, z16;
+    uint32_t q8[8];
+    value_codes8<BITS>(x, lo, hi, s16, z16, q8);
     uint8_t* dst = codes + (size_t)row * (16 * BITS) + c * BITS;
     if constexpr (BITS == 8) {
       uint2 w;

@@ -69,6 +69,12 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     # the long-context shape with 2-bit and 8-bit value codes
     Workload("c3v2_long_context_b4_32k_v2", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=2),
     Workload("c3v8_long_context_b4_32k_v8", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, vbits=8),
+    # the paper's operating point: 256 + 128 code bits per key (3 bits per coordinate) and 4-bit values, on the
+    # long-context and grouped-query shapes; and a whole generation step (append key and value, then attend)
+    Workload("c3o_long_context_b4_32k_dual_v4", 4, 32, 32, 32768, 128, 256, torch.bfloat16, _RS, 1003, 3, m_out=128, vbits=4),
+    Workload("c5bo_llama3_8b_gqa_b16_8k_dual_v4", 16, 32, 8, 8192, 128, 256, torch.bfloat16, _RS, 1006, 5, m_out=128, vbits=4),
+    Workload("c2o_llama2_7b_generation_step_4k_dual_v4", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, m_out=128,
+             vbits=4, stream=True),
     # a whole generation step on the headline shape: append the newest key (Algorithm 1's loop), then attend
     Workload("c2s_llama2_7b_decode_step_4k", 1, 32, 32, 4096, 128, 256, torch.bfloat16, _RS, 1002, 2, stream=True),
 ]}
