@@ -53,10 +53,10 @@ enum {
 enum { QJL_F32 = 0, QJL_F16 = 1, QJL_BF16 = 2 };
 
 typedef struct {
-  int32_t batch;    /* B   >= 1 */
+  int32_t batch;    /* B   >= 1; B * Hq < 2^31 and B * Hkv * n <= 2^40, else QJL_ERR_UNSUPPORTED */
   int32_t q_heads;  /* Hq  >= 1, a multiple of kv_heads */
   int32_t kv_heads; /* Hkv >= 1 */
-  int32_t n;        /* number of cached keys per (batch, kv head), >= 1 */
+  int32_t n;        /* number of cached keys per (batch, kv head), >= 1; the decode calls take up to 2^30 */
   int32_t d;        /* head dimension; this build: 128 */
   int32_t m;        /* sketch dimension; this build: 128, 256 or 512 */
   int32_t dtype;    /* QJL_F32 / QJL_F16 / QJL_BF16: type of K, Q, V and S */

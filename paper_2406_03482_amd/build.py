@@ -54,5 +54,41 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def build_host_sanitizer_driver(verbose: bool = False) -> str:
+    """The library's sources compiled with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code only
+    (the device code is compiled as usual and never runs), linked with tests/host/abi_sanitize.cpp into an
+    executable that exercises what the host decides by itself: argument validation and the decode planner.
+    Returns the executable's path; rebuilt only when a source is newer."""
+    objdir = os.path.join(HERE, "_build", "host_sanitize")
+    os.makedirs(objdir, exist_ok=True)
+    exe = os.path.join(objdir, "abi_sanitize")
+    driver = os.path.join(ROOT, "tests", "host", "abi_sanitize.cpp")
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [driver, os.path.join(ROOT, "include", "qjl.h")]
+    if os.path.exists(exe) and all(os.path.getmtime(exe) >= os.path.getmtime(d) for d in deps):
+        return exe
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g"] + san
+    procs = []
+    for src in SOURCES:
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        cmd = [hipcc(), *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    objs = []
+    for src, obj, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc (host sanitizers) failed on {src}:\n" + out)
+        objs.append(obj)
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O1", "-g", *san, "-I", os.path.join(ROOT, "include"), "-x", "hip", driver,
+           "-x", "none", *objs, "-o", exe]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link of the sanitizer driver failed:\n" + r.stdout)
+    if verbose:
+        print(f"built {exe}")
+    return exe
+
+
 if __name__ == "__main__":
     build(extra_flags=sys.argv[1:])

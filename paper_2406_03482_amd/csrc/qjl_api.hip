@@ -15,9 +15,12 @@ int check_shape(const qjl_shape* sh) {
   if (sh->q_heads % sh->kv_heads != 0) return QJL_ERR_INVALID_ARG;
   if (!dtype_ok(sh->dtype)) return QJL_ERR_INVALID_ARG;
   if (!(sh->scale == sh->scale)) return QJL_ERR_INVALID_ARG;  // NaN
-  // index arithmetic inside the kernels is 64-bit, but tile counts are int
-  const long rows = (long)sh->batch * sh->kv_heads * sh->n;
-  if (rows > (1L << 40)) return QJL_ERR_UNSUPPORTED;
+  // index arithmetic inside the kernels is 64-bit, but tile and head counts are int: at most 2^40 cached
+  // keys and 2^31 - 1 query heads in all (the products are formed with overflow checks: each factor may be
+  // anything up to INT_MAX)
+  long rows = (long)sh->batch * sh->kv_heads;            // < 2^62
+  if (__builtin_mul_overflow(rows, (long)sh->n, &rows) || rows > (1L << 40)) return QJL_ERR_UNSUPPORTED;
+  if ((long)sh->batch * sh->q_heads > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   return QJL_OK;
 }
 

@@ -841,6 +841,7 @@ int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& d
 // shorter context (the rounded count is not monotonic in n).
 bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_splits) {
   if (sh.d != kD) return false;
+  if (sh.n > (1 << 30)) return false;               // key indices and chunk bounds are 32-bit in the kernel
   if (m_out == 0) {
     if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
   } else if (m_out != 128 || (sh.m != 128 && sh.m != 256)) {
