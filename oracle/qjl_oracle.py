@@ -57,10 +57,16 @@ Readings of points the paper leaves open (all restated where they are used):
     [0, 2^b - 1], taken against the *stored* zero point and scale; b = 2, 4 or 8;
     element t of a row occupies bits [b*t, b*t + b) of the row's bytes, LSB
     first; a value is read back as min + code * scale.  The code is an integer
-    decided by floating point, so it is computed in float32 with exactly the
-    operations written in `quantize_values` (the GPU uses the same ones);
-    everything after the code is float64.  Pinned by
-    tests/test_oracle_value_pins.py (round-trip bound, worked example,
+    decided by floating point.  Its definition is `value_codes_exact`: the
+    quotient in exact arithmetic (float64 on exactly represented operands),
+    rounded half to even; entries whose quotient is within 2^-20 relative of
+    a half-integer form the band in which a float32 evaluation may
+    legitimately differ.  `quantize_values` is one such evaluation, with the
+    three float32 operations written out, kept because an implementation that
+    performs the same three operations must then match it bit for bit; it is
+    itself held to `value_codes_exact` outside the band.  Everything after
+    the code is float64.  Pinned by tests/test_oracle_value_pins.py (exact
+    rational arithmetic on small rows, round-trip bound, worked example,
     invariances); the choice of scheme itself is this build's reading.
   * Orthogonalised sketch (Section 4.1, "Orthogonalized JL transform"): the
     paper draws S i.i.d. Gaussian and orthogonalises its rows by QR; with
@@ -409,6 +415,62 @@ def quantize_values(V: np.ndarray, vbits: int = 4):
     for t in range(per):
         packed |= grouped[..., t] << (vbits * t)
     return packed.astype(np.uint8), scale16, zero16
+
+
+def value_codes_exact(V: np.ndarray, scale16: np.ndarray, zero16: np.ndarray, vbits: int = 4):
+    """Section 3.2's rounding step with no float32 in it: against stored constants scale16 / zero16 [B,Hkv,n], the
+    code of entry t is  clip( round_half_even( (v_t - zero) / scale ), 0, 2^b - 1 )  with the quotient formed in
+    float64 from exactly represented operands (its error, 2^-52 relative, is far below anything float32 can
+    resolve).  Returns (codes_per_entry uint8 [B,Hkv,n,d], near_tie bool [B,Hkv,n,d]): near_tie marks the entries
+    whose quotient lies within 2^-20 * max(1, quotient) of a half-integer -- there, and only there, an evaluation
+    of the same three operations in float32 (subtract 2^-24, divide 2^-24 relative) may round to the neighbouring
+    code.  This is the definition that `quantize_values` (which fixes float32) is held to outside that band."""
+    if vbits not in (2, 4, 8):
+        raise ValueError("vbits must be 2, 4 or 8")
+    V = np.asarray(V, dtype=np.float64)
+    sc = np.asarray(scale16, dtype=np.float16).astype(np.float64)[..., None]
+    z = np.asarray(zero16, dtype=np.float16).astype(np.float64)[..., None]
+    levels = float((1 << vbits) - 1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = (V - z) / sc
+    q = np.where(sc > 0, q, 0.0)
+    codes = np.clip(np.rint(q), 0.0, levels).astype(np.uint8)
+    frac = np.abs(q - np.floor(q) - 0.5)
+    inside = (q > -0.5 - 1e-3) & (q < levels + 0.5 + 1e-3)          # ties beyond the clip change nothing
+    near_tie = (frac <= 2.0 ** -20 * np.maximum(1.0, np.abs(q))) & inside & (sc > 0)
+    return codes, near_tie
+
+
+def value_constants_exact(V: np.ndarray, vbits: int = 4):
+    """The stored constants of a row from float64 arithmetic: zero16 = binary16(min), scale16 =
+    binary16((max - min) / (2^b - 1)), and `near_tie` [B,Hkv,n]: rows whose exact scale lies within 2^-21 relative of
+    the midpoint of two neighbouring binary16 numbers, where forming it in float32 first (two roundings of 2^-24)
+    may land on the neighbour."""
+    V = np.asarray(V, dtype=np.float64)
+    levels = float((1 << vbits) - 1)
+    lo, hi = V.min(axis=-1), V.max(axis=-1)
+    exact = (hi - lo) / levels
+    scale16 = exact.astype(np.float16)
+    zero16 = lo.astype(np.float16)
+    s = scale16.astype(np.float64)
+    up = np.nextafter(scale16, np.float16(np.inf)).astype(np.float64)
+    dn = np.nextafter(scale16, np.float16(-np.inf)).astype(np.float64)
+    with np.errstate(invalid="ignore"):
+        d_mid = np.minimum(np.abs(exact - 0.5 * (s + up)), np.abs(exact - 0.5 * (s + dn)))
+    near_tie = d_mid <= 2.0 ** -21 * np.abs(exact)
+    return scale16, zero16, near_tie
+
+
+def unpack_value_codes(codes: np.ndarray, vbits: int = 4) -> np.ndarray:
+    """Packed code bytes [..., d*vbits/8] -> one code per entry, uint8 [..., d] (element t in bits
+    [vbits*t, vbits*t + vbits) of the row, LSB first)."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    per = 8 // vbits
+    mask = (1 << vbits) - 1
+    out = np.empty(codes.shape[:-1] + (codes.shape[-1] * per,), dtype=np.uint8)
+    for t in range(per):
+        out[..., t::per] = (codes >> (vbits * t)) & mask
+    return out
 
 
 def dequantize_values(codes: np.ndarray, scale16: np.ndarray, zero16: np.ndarray, vbits: int = 4) -> np.ndarray:

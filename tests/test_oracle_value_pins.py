@@ -166,3 +166,67 @@ def test_planted_mistake_in_value_functions_is_caught(monkeypatch, name, replace
         except (AssertionError, ValueError, IndexError):
             failed += 1
     assert failed >= 1, f"no pin noticed: {what}"
+
+
+# ------------------------------------------------------------------ the definition in exact arithmetic
+@pytest.mark.parametrize("vbits", [2, 4, 8])
+def test_exact_codes_against_rational_arithmetic(vbits):
+    """`value_codes_exact` against Python's Fraction: (v - zero) / scale as an exact rational, rounded half to even,
+    clipped.  Rows with many exact ties (few-bit inputs) are included on purpose."""
+    from fractions import Fraction
+    rng = np.random.default_rng(40 + vbits)
+    rows = [rng.standard_normal(16).astype(np.float32), np.round(rng.standard_normal(16) * 4) / 8,
+            np.arange(16, dtype=np.float64) * 0.25 - 1.0, np.full(16, 0.75),
+            np.array([0.0, (1 << vbits) - 1, 0.5, 1.5, 2.5, 0.25, 0.75, 1.0, 2.0, 0.5, 1.5, 2.5, 0.0, 1.25, 2.75, 0.5])]   # scale 1: exact ties
+    V = np.stack(rows).astype(np.float32).astype(np.float64)[None, None]
+    sc16, z16, _ = orc.value_constants_exact(V, vbits)
+    codes, near = orc.value_codes_exact(V, sc16, z16, vbits)
+    levels = (1 << vbits) - 1
+    ties = 0
+    for r in range(V.shape[2]):
+        s, z = Fraction(float(sc16[0, 0, r])), Fraction(float(z16[0, 0, r]))
+        for t in range(16):
+            if s == 0:
+                want = 0
+            else:
+                q = (Fraction(float(V[0, 0, r, t])) - z) / s
+                fl = q.numerator // q.denominator
+                rem = q - fl
+                want = fl + 1 if rem > Fraction(1, 2) else fl if rem < Fraction(1, 2) else fl + (fl % 2)
+                ties += rem == Fraction(1, 2)
+                want = min(max(want, 0), levels)
+            assert int(codes[0, 0, r, t]) == want, (r, t)
+    assert ties > 0                                            # the half-even rule was exercised
+    assert near[0, 0, 4, 2:5].all()                            # and those entries are flagged as near a tie
+
+
+@pytest.mark.parametrize("vbits", [2, 4, 8])
+def test_float32_form_agrees_with_the_definition_outside_the_tie_band(vbits):
+    """`quantize_values` (three float32 operations) may differ from the exact definition only where the definition
+    itself flags a near-tie; constants likewise only on rows flagged as near a binary16 midpoint."""
+    rng = np.random.default_rng(50 + vbits)
+    V = (rng.standard_normal((2, 2, 400, 128)) * rng.uniform(0.05, 40.0, size=(2, 2, 400, 1))).astype(np.float32)
+    V[0, 0, :50] = np.round(V[0, 0, :50] * 8) / 8              # bf16-like inputs: exact ties occur
+    V = V.astype(np.float64)
+    packed, sc, z = orc.quantize_values(V, vbits)
+    sc_x, z_x, near_c = orc.value_constants_exact(V, vbits)
+    assert np.array_equal(z.view(np.uint16), z_x.view(np.uint16))
+    assert np.array_equal(sc.view(np.uint16)[~near_c], sc_x.view(np.uint16)[~near_c])
+    codes_x, near = orc.value_codes_exact(V, sc, z, vbits)      # against the constants that were stored
+    got = orc.unpack_value_codes(packed, vbits)
+    diff = got != codes_x
+    assert not (diff & ~near).any()
+    assert int(np.abs(got.astype(int) - codes_x.astype(int)).max()) <= 1
+    assert near.mean() < 0.02                                  # the band is thin
+
+
+def test_unpack_value_codes_is_the_inverse_of_the_packing():
+    rng = np.random.default_rng(9)
+    for vbits in (2, 4, 8):
+        V = rng.standard_normal((1, 2, 5, 32)).astype(np.float32).astype(np.float64)
+        packed, sc, z = orc.quantize_values(V, vbits)
+        per = orc.unpack_value_codes(packed, vbits)
+        for idx in [(0, 0, 0), (0, 1, 4)]:
+            assert per[idx].tolist() == _unpack_loops(packed[idx], vbits, 32)
+        assert np.array_equal(orc.dequantize_values(packed, sc, z, vbits),
+                              z.astype(np.float64)[..., None] + per * sc.astype(np.float64)[..., None])
