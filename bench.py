@@ -370,10 +370,13 @@ def measure_ceilings(ev, dev, quick=False):
     return out
 
 
-def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
+def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup, zero_operands=False):
     import torch
     K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, dev, w.outliers)
     S = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    if zero_operands:       # the same instruction stream on all-zero keys and sketch: no data toggling in the
+        K.zero_()           # matrix pipe or on the memory path (a power experiment, not a workload)
+        S.zero_()
     mt = w.m + w.m_out
     bits = torch.empty((w.batch, w.kv_heads, w.n, mt // 8), dtype=torch.uint8, device=dev)
     norms = torch.empty((w.batch, w.kv_heads, w.n), dtype=torch.float16, device=dev)
@@ -395,7 +398,7 @@ def bench_quantize(qjl, inputs, ev, w, dev, steps, warmup):
     achieved = flops / (ms * 1e-3) / 1e12
     algo_bytes = rows * (w.d * 2 + mt // 8 + (4 if w.m_out else 2))
     return {
-        "workload": w.name,
+        "workload": w.name + ("_zero_operands" if zero_operands else ""),
         "metric": "prefill quantize tokens/s",
         "value": w.batch * w.n / (ms * 1e-3),
         "rows_per_s": rows / (ms * 1e-3),
@@ -592,6 +595,8 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baselines")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the streaming-read and MFMA-loop calibration")
+    ap.add_argument("--zero-operands", action="store_true", help="c4 / c4d only: time the quantizer on all-zero keys and sketch "
+                    "(same instructions, no data toggling: shows how far the kernel is limited by power rather than by issue)")
     ap.add_argument("--cold", action="store_true", help="with --no-extra: also time the headline workload on rotating copies of its cache")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -634,7 +639,7 @@ def main() -> int:
         return 2
     w = inputs.WORKLOADS[names[args.workload]]
     if args.workload.startswith("c4"):
-        head = bench_quantize(qjl, inputs, ev, w, dev, args.steps, args.warmup)
+        head = bench_quantize(qjl, inputs, ev, w, dev, args.steps, args.warmup, zero_operands=args.zero_operands)
         head["ms_per_step_eager"] = head["ms_per_step"]
         r = {"graph_batch": 0}
     else:
@@ -658,7 +663,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
+        "config": {"workload": head.get("workload", w.name), "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "context": w.n, "d": w.d, "m": w.m, "m_out": w.m_out, "vbits": w.vbits, "launch": f"hip graph of {r['graph_batch']} steps" if r["graph_batch"] else "eager, one kernel per step"},
         "roofline": head["roofline"],
         "ceilings": dict(CEIL) if CEIL else None,
