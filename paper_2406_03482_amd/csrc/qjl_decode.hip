@@ -167,19 +167,20 @@ __device__ __forceinline__ float dot8(const slice8<f32_t>& s, const slice8<f32_t
 // are already restricted to the coordinates of each instance, so S q needs no
 // special case, and the two partial inner products are weighted separately.
 // ... or b bytes: eight b-bit codes of a quantized value row (Section 3.2), b = 2, 4
-// or 8.  The codes come out as floats 0 .. 2^b - 1; scale and zero point are
-// applied per row.  Every code is first moved into a byte of its own, then one
-// v_cvt_f32_ubyteN per code.  The conversions are written as asm because the
+// or 8.  The codes come out as floats proportional to 0 .. 2^b - 1; scale and zero
+// point are applied per row.  Every code is first moved into a byte of its own.
+// Eight-bit codes: one v_cvt_f32_ubyteN per code, written as asm because the
 // compiler otherwise extracts every code with its own bit-field instruction.
+// Two- and four-bit codes: a byte that holds a code c <= 15 is, read as an 8-bit float (1-4-3), exactly c * 2^-9
+// (subnormal c/8 * 2^-6 below 8, (1 + (c-8)/8) * 2^-6 from 8 on), and v_cvt_pk_f32_fp8 converts two such bytes per
+// instruction: four conversions instead of eight.  The factor 2^9 goes into the weight of the row, once per key.
+constexpr float kSmallCodeUnit = 0x1.0p-9f;
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void bytes_to_floats(uint32_t even, uint32_t odd, float (&x)[8]) {
-  asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[0]) : "v"(even));
-  asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(x[1]) : "v"(odd));
-  asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[2]) : "v"(even));
-  asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(x[3]) : "v"(odd));
-  asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[4]) : "v"(even));
-  asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(x[5]) : "v"(odd));
-  asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[6]) : "v"(even));
-  asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(x[7]) : "v"(odd));
+  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)even, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)even, true);
+  const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8((int)odd, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)odd, true);
+  x[0] = a[0]; x[2] = a[1]; x[4] = b[0]; x[6] = b[1];
+  x[1] = c[0]; x[3] = c[1]; x[5] = d[0]; x[7] = d[1];
 }
 template <int BITS> struct vtile_q;
 template <> struct vtile_q<4> {
@@ -458,7 +459,7 @@ decode_kernel(decode_args a) {
           uint32_t q8[8];
           value_codes8<VB>(vnew, lo, hi, s16, z16, q8);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) newval[tid * 8 + e] = (float)q8[e];
+          for (int e = 0; e < 8; ++e) newval[tid * 8 + e] = (float)q8[e] * (VB == 8 ? 1.f : kSmallCodeUnit);
           if (tid == 0) { newval_u[0] = s16; newval_u[1] = z16; }
           if constexpr (VB == 8) {
             newval_u[2 + 2 * tid] = q8[0] | (q8[1] << 8) | (q8[2] << 16) | (q8[3] << 24);
@@ -518,7 +519,8 @@ decode_kernel(decode_args a) {
     const bool valid = (k0 + lane) < k_end;
     const float nu = f16_bits_to_float(ncur) * a.coef2;
     const float nu2 = MWB > 0 ? f16_bits_to_float(ncur2) * a.coef2b : 0.f;
-    const float vs = VQ ? f16_bits_to_float(vscur) : 1.f;
+    // (codes of 2 and 4 bits reach the value pass as c * 2^-9)
+    const float vs = VQ ? f16_bits_to_float(vscur) * (VB == 8 ? 1.f : 1.f / kSmallCodeUnit) : 1.f;
     const float vz = VQ ? f16_bits_to_float(vzcur) : 0.f;
     // the code registers are free again: fetch the next block's codes and norm
     // into them now, the value pass below hides the latency
