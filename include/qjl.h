@@ -270,7 +270,8 @@ size_t qjl_decode_dual_workspace_bytes(const qjl_shape* shape, int m_out);
  *   score_j = scale * sqrt(pi/2) * ( norms_in[j]/m * <S_in q_in, inlier bits_j>
  *                                  + norms_out[j]/m_out * <S_out q_out, outlier bits_j> )
  * then softmax and Eq. (1).  S_dual as written by qjl_make_dual_sketch.
- * Supported: d == 128, m in {128, 256}, m_out == 128.  Workspace rules as for
+ * Supported: d == 128 and (m, m_out) in {(128,128), (256,128), (512,128),
+ * (256,256)}.  Workspace rules as for
  * qjl_decode_attention; event_before / event_after (may be NULL) as in
  * qjl_decode_attention_timed.
  */

@@ -299,6 +299,7 @@ int qjl_decode_attention_dual_vq(const qjl_shape* shape, int m_out, int vbits, c
     return QJL_ERR_INVALID_ARG;
   if (m_out < 1 || vbits < 1 || vbits > 8) return QJL_ERR_INVALID_ARG;
   if ((vbits != 2 && vbits != 4 && vbits != 8) || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
+  if (m_out != 128 || (shape->m != 128 && shape->m != 256)) return QJL_ERR_UNSUPPORTED;
   decode_plan plan;
   if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
   if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
@@ -321,6 +322,7 @@ int qjl_generation_step(const qjl_shape* shape, int m_out, int vbits, int pos, c
   if (m_out < 1 || vbits < 1 || vbits > 8 || count < 0 || count > 16) return QJL_ERR_INVALID_ARG;
   if (pos < 0 || pos >= shape->n) return QJL_ERR_INVALID_ARG;
   if ((vbits != 2 && vbits != 4 && vbits != 8) || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
+  if (m_out != 128 || (shape->m != 128 && shape->m != 256)) return QJL_ERR_UNSUPPORTED;
   qjl_shape now = *shape;                          // attention covers rows 0..pos of caches with shape->n rows
   now.n = pos + 1;
   decode_plan plan;

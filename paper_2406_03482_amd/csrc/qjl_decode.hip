@@ -790,6 +790,11 @@ int launch_m(const qjl_shape& sh, int m_out, int vbits, const decode_plan& plan,
   }
   if (m_out == 128 && sh.m == 128) return launch_v<T, 8, 4>(sh, vbits, ap, plan, a, st, ev0, ev1);
   if (m_out == 128 && sh.m == 256) return launch_v<T, 12, 4>(sh, vbits, ap, plan, a, st, ev0, ev1);
+  // larger two-part codes: unquantized values, no streaming
+  if (vbits == 0 && !ap) {
+    if (m_out == 128 && sh.m == 512) return launch_g<T, 20, 4>(sh, plan, a, st, ev0, ev1);
+    if (m_out == 256 && sh.m == 256) return launch_g<T, 16, 8>(sh, plan, a, st, ev0, ev1);
+  }
   return QJL_ERR_UNSUPPORTED;
 }
 
@@ -846,7 +851,7 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_sp
   if (sh.n > (1 << 30)) return false;               // key indices and chunk bounds are 32-bit in the kernel
   if (m_out == 0) {
     if (sh.m != 128 && sh.m != 256 && sh.m != 512) return false;
-  } else if (m_out != 128 || (sh.m != 128 && sh.m != 256)) {
+  } else if (!((m_out == 128 && (sh.m == 128 || sh.m == 256 || sh.m == 512)) || (m_out == 256 && sh.m == 256))) {
     return false;
   }
   const int mt = sh.m + m_out;                      // all code bits of a key

@@ -81,7 +81,7 @@ int main() {
   const int heads[][2] = {{1, 1}, {32, 32}, {32, 8}, {6, 2}, {3, 1}, {64, 1}, {4096, 512}};
   const int batches[] = {1, 4, 16, 4096, 1 << 20};
   const int splits[] = {0, 1, 2, 7, 64, 512, 513, 4096, INT_MAX};
-  const int ms[][2] = {{128, 0}, {256, 0}, {512, 0}, {128, 128}, {256, 128}};
+  const int ms[][2] = {{128, 0}, {256, 0}, {512, 0}, {128, 128}, {256, 128}, {512, 128}, {256, 256}};
   long plans = 0;
   for (int n : ns) for (auto& h : heads) for (int b : batches) for (auto& mm : ms) for (int dt : {QJL_F32, QJL_BF16}) {
     const qjl_shape s = shape(b, h[0], h[1], n, 128, mm[0], dt);

@@ -145,7 +145,10 @@ def test_dual_entry_points_validate_on_the_host(L):
     assert L.qjl_outlier_workspace_bytes(ctypes.byref(sh)) == 1 * 2 * 1 * 128 * 4
     assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(sh), 128) > 0
     assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(sh), 64) == 0       # unsupported split
-    bad = QJLShape(1, 4, 2, 100, 128, 512, 2, 1.0)
+    big = QJLShape(1, 4, 2, 100, 128, 512, 2, 1.0)
+    assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(big), 128) > 0       # 512 + 128 bits: built
+    assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(big), 256) == 0      # 512 + 256: not
+    bad = QJLShape(1, 4, 2, 100, 128, 384, 2, 1.0)
     assert L.qjl_decode_dual_workspace_bytes(ctypes.byref(bad), 128) == 0
     # count out of range / null pointers
     assert L.qjl_select_outliers(ctypes.byref(sh), ok, 0, ok, ok, ctypes.c_size_t(1 << 20), None) == INVALID

@@ -195,6 +195,10 @@ DUAL_DECODE_CASES = [
     ("bf16", 1, 2, 2, 1, 256, 128, 1.0),          # n = 1
     ("bf16", 1, 1, 1, 65, 256, 128, 0.0884),
     ("bf16", 1, 2, 1, 20000, 256, 128, 0.0884),   # many chunks
+    ("bf16", 2, 4, 2, 900, 512, 128, 0.0884),     # 640-bit codes: one head at a time
+    ("f16", 1, 4, 4, 300, 512, 128, 1.0),
+    ("bf16", 1, 8, 2, 1200, 256, 256, 0.0884),    # 512-bit codes with a 256-bit outlier part, GQA x4 -> two heads at a time
+    ("f32", 1, 2, 1, 200, 256, 256, 0.0884),
 ]
 
 
