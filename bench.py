@@ -335,7 +335,7 @@ def measure_ceilings(ev, dev, quick=False):
         bufs = [torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device=dev, generator=g) for _ in range(nsets)]
         reps = 20 if quick else (200 if nbytes < 100e6 else 60)
         # the ceiling is the best of a few launch shapes (workgroups per CU x load kind x access pattern)
-        shapes = [(cus * k, mode) for k in (2, 4, 8, 16) for mode in range(4)]
+        shapes = [(cus * k, mode) for k in (2, 4, 8, 16) for mode in range(5)]
         def sweep(pick):
             best = None
             for blocks, mode in shapes:

@@ -30,6 +30,28 @@ template <bool NT> __device__ __forceinline__ u32x4_t ld16(const u32x4_t* p) {
   else return *p;
 }
 
+// Workgroup b reads the pieces b, b + grid, b + 2 grid, ... of 64 KB each (non-temporal loads): every
+// workgroup walks the whole buffer front to back, all of them close together.
+__global__ void __launch_bounds__(256) stream_read_cyclic_kernel(const u32x4_t* __restrict__ src, size_t n16,
+                                                                 uint32_t* __restrict__ sink) {
+  constexpr size_t kPiece16 = 4096;                     // 64 KB
+  const size_t pieces = (n16 + kPiece16 - 1) / kPiece16;
+  u32x4_t acc = {0u, 0u, 0u, 0u};
+  for (size_t c = blockIdx.x; c < pieces; c += gridDim.x) {
+    const u32x4_t* p = src + c * kPiece16;
+    const int end = (int)min(kPiece16, n16 - c * kPiece16);
+    for (int i = threadIdx.x; i < end; i += 256 * kReadUnroll) {
+      u32x4_t v[kReadUnroll];
+#pragma unroll
+      for (int u = 0; u < kReadUnroll; ++u) v[u] = (i + u * 256 < end) ? __builtin_nontemporal_load(p + i + u * 256) : acc;
+#pragma unroll
+      for (int u = 0; u < kReadUnroll; ++u) acc ^= v[u];
+    }
+  }
+  const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+  if (x == 0x9E3779B9u && sink != nullptr) sink[0] = x;
+}
+
 // NT: loads marked non-temporal.  CHUNKED: a workgroup reads one contiguous piece of the buffer (the way a
 // decode workgroup reads its chunk of the context); otherwise consecutive workgroups read consecutive 4 KB.
 template <bool NT, bool CHUNKED>
@@ -119,9 +141,10 @@ __global__ void __launch_bounds__(512, 1) mfma_loop_kernel(const u32x4_t* __rest
 extern "C" {
 
 // Reads `bytes` (a multiple of 16) from src once.  grid_blocks workgroups of 256 threads.
-// mode bit 0: non-temporal loads; bit 1: one contiguous piece per workgroup.
+// mode bit 0: non-temporal loads; bit 1: one contiguous piece per workgroup; mode 4: 64 KB pieces dealt
+// round-robin to the workgroups, non-temporal.
 int ceil_stream_read(const void* src, size_t bytes, int grid_blocks, int mode, void* sink, void* stream) {
-  if (src == nullptr || bytes == 0 || bytes % 16 != 0 || grid_blocks < 1 || mode < 0 || mode > 3) return -1;
+  if (src == nullptr || bytes == 0 || bytes % 16 != 0 || grid_blocks < 1 || mode < 0 || mode > 4) return -1;
   const dim3 grid((unsigned)grid_blocks), block(256);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const u32x4_t* p = static_cast<const u32x4_t*>(src);
@@ -130,6 +153,7 @@ int ceil_stream_read(const void* src, size_t bytes, int grid_blocks, int mode, v
     case 0: hipLaunchKernelGGL((stream_read_kernel<false, false>), grid, block, 0, st, p, bytes / 16, k); break;
     case 1: hipLaunchKernelGGL((stream_read_kernel<true, false>), grid, block, 0, st, p, bytes / 16, k); break;
     case 2: hipLaunchKernelGGL((stream_read_kernel<false, true>), grid, block, 0, st, p, bytes / 16, k); break;
+    case 4: hipLaunchKernelGGL(stream_read_cyclic_kernel, grid, block, 0, st, p, bytes / 16, k); break;
     default: hipLaunchKernelGGL((stream_read_kernel<true, true>), grid, block, 0, st, p, bytes / 16, k); break;
   }
   return hipGetLastError() == hipSuccess ? 0 : -4;
