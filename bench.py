@@ -508,6 +508,27 @@ def bench_sketches(qjl, ev, dev):
     return out
 
 
+def bench_outlier_setup(qjl, inputs, ev, w, dev):
+    """Prompt-phase set-up of the two-part code (Section 4.1) on the prefill keys: the per-channel magnitude pass
+    with the selection of the outlier channels (reads every key once: 256 B per key and head against HBM), and
+    the stacked per-head sketch."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    K = inputs.make_keys(w.batch, w.kv_heads, w.n, w.d, w.dtype, w.data_seed, dev, w.outliers)
+    S_in = qjl.qjl_make_sketch(w.sketch_seed, w.m, w.d, w.dtype, dev)
+    S_out = qjl.qjl_make_sketch(w.sketch_seed + 1000, w.m_out, w.d, w.dtype, dev)
+    ch = torch.empty((w.batch, w.kv_heads, 4), dtype=torch.int32, device=dev)
+    ws = torch.empty((1 << 24,), dtype=torch.uint8, device=dev)
+    S_dual = qjl.qjl_make_dual_sketch(S_in, S_out, qjl.qjl_select_outliers(K, 4, channels=ch, workspace=ws))
+    ms_sel = timed_launches(ev, stream, lambda i: qjl.qjl_select_outliers(K, 4, channels=ch, workspace=ws), 20, 3)
+    ms_dual = timed_launches(ev, stream, lambda i: qjl.qjl_make_dual_sketch(S_in, S_out, ch, S_dual), 20, 3)
+    nbytes = K.numel() * K.element_size()
+    return {"workload": w.name + "_outlier_setup", "metric": "set-up kernel time", "unit": "us",
+            "select_outliers_us": ms_sel * 1e3, "select_outliers_GBs": nbytes / (ms_sel * 1e-3) / 1e9,
+            "select_outliers_frac_of_hbm_peak": nbytes / (ms_sel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "make_dual_sketch_us": ms_dual * 1e3}
+
+
 def _oracle_threads():
     from threadpoolctl import threadpool_info
     return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -699,6 +720,7 @@ def main() -> int:
         extra.append(bench_value_quantize(qjl, inputs, ev, inputs.WORKLOADS["c4_prefill_quantize_64k"], dev, 50, 5))
         extra.append(bench_scores(qjl, inputs, ev, inputs.WORKLOADS["c3_long_context_b4_32k"], dev, 100, 10))
         line["setup_kernels"] = bench_sketches(qjl, ev, dev)
+        line["setup_kernels_outliers"] = bench_outlier_setup(qjl, inputs, ev, inputs.WORKLOADS["c4d_prefill_quantize_64k_dual"], dev)
         line["other_workloads"] = extra
 
     line["cpu_baseline"] = None

@@ -27,11 +27,23 @@ abs_sum128_kernel(const void* __restrict__ K, float* __restrict__ part, int n, i
   const int j0 = blockIdx.x * kRowsPerSplit;
   const int j1 = min(n, j0 + kRowsPerSplit);
   float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int j = j0 + r; j < j1; j += 16) {
-    float x[8];
-    load8<T>(K, (seg * (size_t)n + j) * 128 + c * 8, x);
+  // eight rows requested before the first is used (one load in flight per thread leaves the
+  // memory system idle); they are added in row order, as a one-row-at-a-time loop would
+  constexpr int kAhead = 8;
+  for (int j = j0 + r; j < j1; j += 16 * kAhead) {
+    float x[kAhead][8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s[e] += fabsf(x[e]);
+    for (int u = 0; u < kAhead; ++u) {
+      const int ju = min(j + 16 * u, j1 - 1);           // rows past the split: a row inside it, not added
+      load8<T>(K, (seg * (size_t)n + ju) * 128 + c * 8, x[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      if (j + 16 * u < j1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += fabsf(x[u][e]);
+      }
+    }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[r][c * 8 + e] = s[e];
@@ -59,8 +71,10 @@ abs_sum_generic_kernel(const void* __restrict__ K, float* __restrict__ part, int
 }
 
 // Add the splits (fixed order) and pick the `count` largest sums.  One workgroup
-// per (batch, kv head); the selection itself is a short serial scan by thread 0
-// (d * count comparisons), which makes the tie rule explicit.
+// per (batch, kv head).  The selection is done by the first wave: every lane scans
+// the channels lane, lane + 64, ... in increasing order (a strictly larger sum
+// replaces the candidate, so the lower index wins a tie inside a lane), then six
+// exchange steps keep the larger sum or, for equal sums, the lower index.
 __global__ void __launch_bounds__(256)
 top_channels_kernel(const float* __restrict__ part, int32_t* __restrict__ channels, int d, int nsplit,
                     int count) {
@@ -72,15 +86,31 @@ top_channels_kernel(const float* __restrict__ part, int32_t* __restrict__ channe
     tot[t] = s;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
     for (int c = 0; c < count; ++c) {
-      int best = 0;
-      float bv = -1.f;
-      for (int t = 0; t < d; ++t) {
-        if (tot[t] > bv) { bv = tot[t]; best = t; }  // strict: the lower index wins a tie
+      float bv = -1.f;                                // sums of magnitudes are >= 0 (a NaN sum is never picked)
+      int best = 0x7FFFFFFF;
+      for (int t = lane; t < d; t += 64) {
+        const float v = tot[t];
+        if (v > bv) { bv = v; best = t; }
       }
-      channels[seg * count + c] = best;
-      tot[best] = -2.f;                               // sums of magnitudes are >= 0: never picked again
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int ob = __shfl_xor(best, off);
+        if (ov > bv || (ov == bv && ob < best)) { bv = ov; best = ob; }
+      }
+      // every lane now holds the same winner; with nothing left to pick (count > d, or only NaN sums)
+      // the serial rule's answer is channel 0
+      if (best == 0x7FFFFFFF) best = 0;
+      if (lane == 0) {
+        channels[seg * count + c] = best;
+        tot[best] = -2.f;                             // never picked again
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   }
 }
