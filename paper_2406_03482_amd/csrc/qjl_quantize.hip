@@ -82,6 +82,14 @@ template <typename T> __device__ __forceinline__ void sumsq8_split(const uint32_
   }
 }
 
+// f(integral_constant<int, I>) for I = 0 .. N-1: indices that are constants to the compiler front end
+template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
 constexpr int kTok = 64;        // keys per tile: two N = 32 MFMA sub-tiles
 constexpr int kRowU4 = 18;      // LDS row pitch in 16-byte units: 256 B of key + 32 B pad (see kSPitch)
 
@@ -174,8 +182,27 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
   // with the 32x32 accumulator layout (register v of lane (h, j) is row
   // 8(v/4) + 4h + v%4) lane (h, j) then owns projections
   // proj_base + h*PPW/2 + 16a + v, v = 0..15 -- consecutive code bits of key j.
-  frag sfrag[NA][8];
+  // PPW == 128 (W16): v_mfma_f32_16x16x32 -- the 32x32x16 form runs at half the rate on this chip.  Eight A
+  // tiles of 16 projections x four steps of 32 elements; lane (q16, j16) = (lane >> 4, lane & 15) holds row
+  // j16, elements 32s + 8 q16 .. + 7.  Row rho of tile a is projection proj_base + 32 (rho >> 2) + 4a + (rho & 3):
+  // accumulator register r of lane (q16, j16) is then projection proj_base + 32 q16 + 4a + r of key j16, so the
+  // lane's 32 sign bits (a = 0..7, r = 0..3) are one whole code word, word wave * 4 + q16 of the key's row.
+  constexpr bool W16 = PPW == 128;
+  const int q16 = lane >> 4, j16 = lane & 15;
+  frag sfrag[W16 ? 8 : NA][W16 ? 4 : 8];
   if (computes) {
+    if constexpr (W16) {
+#pragma unroll
+      for (int a = 0; a < 8; ++a) {
+        const int srow = proj_base + 32 * (j16 >> 2) + 4 * a + (j16 & 3);
+        const uint4* sp = reinterpret_cast<const uint4*>(S + (size_t)srow * 128 + 8 * q16);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          uint4 u = sp[4 * s];
+          __builtin_memcpy(&sfrag[a][s], &u, 16);
+        }
+      }
+    } else {
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
     const int srow = proj_base + ((j >> 2) & 1) * (PPW / 2) + 16 * a + 4 * (j >> 3) + (j & 3);
@@ -186,6 +213,7 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
       __builtin_memcpy(&sfrag[a][s], &u, 16);
     }
   }
+    }
   }
 
   // ---- loader: thread -> (row lrow + 16u, 16-byte column lcol) of a tile, u = 0..3
@@ -276,7 +304,52 @@ quantize_mfma_kernel(const uint16_t* __restrict__ K, const uint16_t* __restrict_
     // u-1 are extracted (v_alignbit) in the shadow of its MFMAs, and the B
     // operand of step g+2 is fetched from LDS, so the matrix pipe never waits
     // for the vector ALU or for LDS.  sched_barrier keeps that interleaving.
+    if constexpr (W16) {
     if (computes) {
+      // A unit = one group of 16 keys against the wave's 128 projections: 4 steps x 8 MFMAs on eight
+      // independent accumulators.  While unit c accumulates, the sign bits of unit c-1 are shifted into its
+      // code word (one v_alignbit per accumulator register, highest bit first), and the B operand of two
+      // steps ahead comes from LDS: 1 KB per eight MFMAs.
+      auto lds_b16 = [&](int g) {                 // step g = 4c + s: key 16c + j16, elements 32s + 8 q16 .. + 7
+        frag f;
+        const uint4 u4 = kbuf[buf][(16 * (g >> 2) + j16) * kRowU4 + 4 * (g & 3) + q16];
+        __builtin_memcpy(&f, &u4, 16);
+        return f;
+      };
+      frag bq[3];
+      bq[0] = lds_b16(0);
+      bq[1] = lds_b16(1);
+      const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+      f32x4_t acc[2][8];
+      uint32_t tb = 0u;
+      uint32_t* ocol = reinterpret_cast<uint32_t*>(obuf[buf]) + j16 * WPT + wave * 4 + q16;
+      static_for<0, 5>([&](auto uc) {             // round 4 only drains the last unit's bits
+        constexpr int u = decltype(uc)::value, par = u & 1;
+        static_for<0, 4>([&](auto sc) {
+          constexpr int s = decltype(sc)::value, g = u * 4 + s;
+          if constexpr (g + 2 < 16) bq[(g + 2) % 3] = lds_b16(g + 2);
+          if constexpr (u < 4) {
+#pragma unroll
+            for (int a = 0; a < 8; ++a)
+              acc[par][a] = mma16<T>::run(sfrag[a][s], bq[g % 3], s == 0 ? zero : acc[par][a]);
+          }
+          if constexpr (u > 0) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+              for (int r = 3; r >= 0; --r)
+                tb = __builtin_amdgcn_alignbit(tb, __float_as_uint(acc[par ^ 1][7 - 2 * s - t][r]), 31);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        if constexpr (u > 0) {
+          asm volatile("" : "+v"(tb));             // the bits are taken here, not where they are stored
+          ocol[(u - 1) * 16 * WPT] = ~tb;         // bit = [acc >= 0]
+          tb = 0u;
+        }
+      });
+    }
+    } else if (computes) {
     constexpr int NU = NA >= 2 ? NA : 1;
     auto sub_of = [](int u, int c) { return NA >= 2 ? u / (NA / 2) : c; };
     auto a_of = [](int u, int c) { return NA >= 2 ? 2 * (u % (NA / 2)) + c : 0; };
@@ -390,14 +463,6 @@ __device__ __forceinline__ float sum_rows4(float x) {
   const uint32_t v = __float_as_uint(y);
   const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);   // {even rows twice, odd rows twice}
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
-
-// f(integral_constant<int, I>) for I = 0 .. N-1: indices that are constants to the compiler front end
-template <int I, int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
 }
 
 // v_mfma_f32_16x16x32: a unit is 16 projections against four sub-tiles of 16

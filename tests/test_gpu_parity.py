@@ -104,6 +104,9 @@ QUANT_CASES = [
     ("bf16", 1, 1, 95, 128, 128, 4),         # MFMA m=128 (32 projections per wave, 16-bit stores)
     ("bf16", 1, 1, 70, 128, 384, 0),         # three blocks of 128 projections
     ("bf16", 1, 1, 33, 128, 1024, 0),        # two blocks of 512 projections
+    ("bf16", 2, 2, 1500, 128, 1024, 4),      # the same over many tiles: sketch rows in registers, keys through LDS
+    ("f16", 1, 3, 700, 128, 768, 4),         # two blocks of 384 projections (three computing waves per workgroup)
+    ("bf16", 1, 2, 300, 128, 640, 4),        # 640 = 5 x 128: 32 projections per wave
     ("f16", 1, 2, 513, 128, 256, 4),         # fp16 MFMA
     ("f16", 1, 1, 64, 128, 512, 0),
     ("bf16", 1, 1, 1, 128, 256, 0),          # a single key
