@@ -385,6 +385,27 @@ int qjl_generation_step(const qjl_shape* shape, int m_out, int vbits, int pos, c
                         uint16_t* norms_out, uint8_t* vcodes, uint16_t* vscale, uint16_t* vzero,
                         float* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The same generation step (Algorithm 1's loop body at the operating point of
+ * Section 4.1 + Section 3.2) with the position read from device memory by the
+ * kernel: a step recorded once into a HIP graph can be replayed for a whole
+ * generation, the caller advancing *pos_dev (device int32) between replays by
+ * work of its own on the same stream.  shape->n is the capacity of the caches.
+ * The context is always cut into the chunks planned for the capacity, so a step
+ * far below the capacity leaves most workgroups without keys (they write an
+ * empty record); qjl_generation_step, which plans for pos + 1, is the faster
+ * call outside graphs.  A value of *pos_dev outside [0, shape->n) cannot be
+ * reported from inside the kernel: it is clamped into that range.  Everything
+ * else -- arguments, supported combinations, workspace (taken at the capacity),
+ * results bit for bit up to the order in which chunks are summed -- as
+ * qjl_generation_step.
+ */
+int qjl_generation_step_devpos(const qjl_shape* shape, int m_out, int vbits, const int32_t* pos_dev,
+                               const void* K_new, const void* V_new, const void* Q, const void* S_dual,
+                               const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                               uint16_t* norms_out, uint8_t* vcodes, uint16_t* vscale, uint16_t* vzero,
+                               float* out, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
     L.qjl_decode_attention_dual_vq.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     L.qjl_generation_step.restype = ctypes.c_int
     L.qjl_generation_step.argtypes = [sp, ip, ip, ip, vp, vp, vp, vp, vp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.qjl_generation_step_devpos.restype = ctypes.c_int
+    L.qjl_generation_step_devpos.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp, vp, ip, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.qjl_append_keys.restype = ctypes.c_int
     L.qjl_append_keys.argtypes = [sp, ip, ip, vp, vp, vp, vp, vp]
     L.qjl_decode_step.restype = ctypes.c_int
@@ -494,11 +496,12 @@ def qjl_decode_attention_dual_vq(Q: torch.Tensor, S_dual: torch.Tensor, bits: to
 
 def qjl_generation_step(Q: torch.Tensor, K_new: torch.Tensor, V_new: torch.Tensor, S_dual: torch.Tensor,
                         channels: torch.Tensor, bits: torch.Tensor, norms_in: torch.Tensor, norms_out: torch.Tensor,
-                        vcodes: torch.Tensor, vscale: torch.Tensor, vzero: torch.Tensor, pos: int, m_out: int,
+                        vcodes: torch.Tensor, vscale: torch.Tensor, vzero: torch.Tensor, pos, m_out: int,
                         vbits: int = 4, scale: float = 1.0, out: Optional[torch.Tensor] = None,
                         workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Append the new token (K_new, V_new [B,Hkv,1,d]) at row pos of the six cache arrays, then attention of
-    Q[B,Hq,d] over rows 0..pos -> float32 [B,Hq,d]."""
+    Q[B,Hq,d] over rows 0..pos -> float32 [B,Hq,d].  pos: an int, or a one-element int32 device tensor that the
+    kernel reads (qjl_generation_step_devpos: for steps replayed from a graph)."""
     B, Hq, d = Q.shape
     _, Hkv, cap, vb = vcodes.shape
     mt = S_dual.shape[2]
@@ -521,6 +524,18 @@ def qjl_generation_step(Q: torch.Tensor, K_new: torch.Tensor, V_new: torch.Tenso
     if out is None:
         out = torch.empty((B, Hq, d), dtype=torch.float32, device=Q.device)
     sh = _shape(B, Hq, Hkv, cap, d, m, _tag(Q), scale)
+    if isinstance(pos, torch.Tensor):               # position in device memory (int32, one element): graph-replayable
+        if pos.dtype != torch.int32 or pos.numel() != 1:
+            raise ValueError("a device position must be one int32")
+        _check("qjl_generation_step_devpos",
+               lib().qjl_generation_step_devpos(ctypes.byref(sh), m_out, vbits, _dev(pos, "pos"), _dev(K_new, "K_new"),
+                                                _dev(V_new, "V_new"), _dev(Q, "Q"), _dev(S_dual, "S_dual"),
+                                                _dev(channels, "channels"), count, _dev(bits, "bits"),
+                                                _dev(norms_in, "norms_in"), _dev(norms_out, "norms_out"),
+                                                _dev(vcodes, "vcodes"), _dev(vscale, "vscale"), _dev(vzero, "vzero"),
+                                                _dev(out, "out"), _dev(workspace, "workspace"),
+                                                workspace.numel() * workspace.element_size(), _stream(Q)))
+        return out
     _check("qjl_generation_step",
            lib().qjl_generation_step(ctypes.byref(sh), m_out, vbits, pos, _dev(K_new, "K_new"), _dev(V_new, "V_new"),
                                      _dev(Q, "Q"), _dev(S_dual, "S_dual"), _dev(channels, "channels"), count,

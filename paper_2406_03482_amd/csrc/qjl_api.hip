@@ -334,6 +334,31 @@ int qjl_generation_step(const qjl_shape* shape, int m_out, int vbits, int pos, c
                        out, workspace, static_cast<hipStream_t>(stream), nullptr, nullptr, K_new, bits, norms_in, &nt);
 }
 
+int qjl_generation_step_devpos(const qjl_shape* shape, int m_out, int vbits, const int32_t* pos_dev,
+                               const void* K_new, const void* V_new, const void* Q, const void* S_dual,
+                               const int32_t* channels, int count, uint8_t* bits, uint16_t* norms_in,
+                               uint16_t* norms_out, uint8_t* vcodes, uint16_t* vscale, uint16_t* vzero, float* out,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != QJL_OK) return rc;
+  if (!ptr_ok(pos_dev) || !ptr_ok(K_new) || !ptr_ok(V_new) || !ptr_ok(Q) || !ptr_ok(S_dual) || !ptr_ok(bits) ||
+      !ptr_ok(norms_in) || !ptr_ok(norms_out) || !ptr_ok(vcodes) || !ptr_ok(vscale) || !ptr_ok(vzero) || !ptr_ok(out) ||
+      (channels == nullptr && count > 0))
+    return QJL_ERR_INVALID_ARG;
+  if (m_out < 1 || vbits < 1 || vbits > 8 || count < 0 || count > 16) return QJL_ERR_INVALID_ARG;
+  if ((vbits != 2 && vbits != 4 && vbits != 8) || shape->dtype == QJL_F32) return QJL_ERR_UNSUPPORTED;
+  if (m_out != 128 || (shape->m != 128 && shape->m != 256)) return QJL_ERR_UNSUPPORTED;
+  decode_plan plan;                                // the chunks are those of the capacity, whatever the position
+  if (!plan_decode(*shape, m_out, &plan)) return QJL_ERR_UNSUPPORTED;
+  if (workspace == nullptr || workspace_bytes < plan.total) return QJL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return QJL_ERR_INVALID_ARG;
+  decode_new_token nt{norms_out, channels, count, V_new, vcodes, vscale, vzero};
+  nt.pos_dev = pos_dev;
+  return launch_decode(*shape, m_out, plan, Q, S_dual, bits, norms_in, norms_out, vcodes, vscale, vzero, vbits,
+                       shape->n, out, workspace, static_cast<hipStream_t>(stream), nullptr, nullptr, K_new, bits,
+                       norms_in, &nt);
+}
+
 int qjl_append_keys(const qjl_shape* shape, int pos, int count, const void* K_new, const void* S,
                     uint8_t* bits, uint16_t* norms, void* stream) {
   int rc = check_shape(shape);

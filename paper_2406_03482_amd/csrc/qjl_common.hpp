@@ -175,6 +175,9 @@ struct decode_new_token {
   uint8_t* vcodes_w;
   uint16_t* vscale_w;
   uint16_t* vzero_w;
+  // not null: the position of the new token is read from device memory by the kernel (sh.n is then the
+  // capacity the plan was made for); values outside [0, sh.n) are clamped into it
+  const int32_t* pos_dev = nullptr;
 };
 int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const void* Q, const void* S,
                   const uint8_t* bits, const uint16_t* norms, const uint16_t* norms_out, const void* V,

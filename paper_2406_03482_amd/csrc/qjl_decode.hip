@@ -68,6 +68,9 @@ struct decode_args {
   uint8_t* vcodes_w;      // the value caches, writable
   uint16_t* vscale_w;
   uint16_t* vzero_w;
+  // Streaming with the position in device memory (a generation loop captured in a graph): n above is then
+  // the capacity the chunks were planned for, and the kernel attends over rows 0 .. *pos_dev.
+  const int32_t* pos_dev; // or null
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -268,8 +271,25 @@ decode_kernel(decode_args a) {
   const int bk = blockIdx.x;                          // b * Hkv + kvh
   const size_t hq0 = ((size_t)bk * a.groups_per_kv + blockIdx.y) * GT;
 
+  int n = a.n;
+  if constexpr (AP) {
+    if (a.pos_dev != nullptr) n = min(max(*a.pos_dev, 0), a.n - 1) + 1;   // uniform: a scalar load
+  }
   const int k_begin = split * a.chunk;
-  const int k_end = min(a.n, k_begin + a.chunk);
+  const int k_end = min(n, k_begin + a.chunk);
+  if constexpr (AP) {
+    // chunks planned for the capacity that lie wholly behind the newest row: an empty record (weight 0 in
+    // the merge) and nothing else
+    if (k_begin >= n) {                               // uniform; never the first chunk
+      for (int idx = threadIdx.x; idx < GT * kD; idx += kNW * 64) {
+        const int g = idx >> 7, ch = idx & 127;
+        float* rec = a.part + ((hq0 + g) * a.nsplit + split) * kPartStride;
+        rec[4 + ch] = 0.f;
+        if (ch == 0) { rec[0] = -INFINITY; rec[1] = 0.f; rec[2] = 0.f; }
+      }
+      return;
+    }
+  }
   const size_t row0 = (size_t)bk * a.n_cap;         // first row of this (batch, kv head) in the caches
   float* pbuf = pbuf_all + wave * 64 * GT;
   int r = lane >> 4;                                  // row of a 4-row V pass
@@ -299,7 +319,7 @@ decode_kernel(decode_args a) {
   // AP: the new key is row n - 1; the workgroups whose chunk holds that row
   // quantize it themselves (same S, same walk as for the queries), use its code
   // from LDS and, the first group of query heads only, write it to the caches.
-  const int pos = a.n - 1;
+  const int pos = n - 1;
   const bool has_new = AP && pos >= k_begin && pos < k_end;   // uniform
   {
     const int c16 = tid & (LPR - 1), r16 = tid / LPR;
@@ -914,6 +934,7 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.vcodes_w = nt ? nt->vcodes_w : nullptr;
   a.vscale_w = nt ? nt->vscale_w : nullptr;
   a.vzero_w = nt ? nt->vzero_w : nullptr;
+  a.pos_dev = nt ? nt->pos_dev : nullptr;
   a.s_head_stride = m_out > 0 ? (size_t)(sh.m + m_out) * kD : 0;
   a.coef2b = m_out > 0 ? sh.scale * 1.2533141373155002512f / (float)m_out * 1.4426950408889634074f : 0.f;
   a.part = reinterpret_cast<float*>(ws + plan.off_part);

@@ -54,6 +54,9 @@ int main() {
   EXPECT(qjl_generation_step(&good, 128, 4, 4096, P, P, P, P, PI, 4, P8, P16, P16, P8, P16, P16, PF, P, 1 << 20, nullptr) == QJL_ERR_INVALID_ARG);
   EXPECT(qjl_generation_step(&good, 128, 4, -1, P, P, P, P, PI, 4, P8, P16, P16, P8, P16, P16, PF, P, 1 << 20, nullptr) == QJL_ERR_INVALID_ARG);
   EXPECT(qjl_generation_step(&good, 128, 4, 7, P, P, P, P, nullptr, 4, P8, P16, P16, P8, P16, P16, PF, P, 1 << 20, nullptr) == QJL_ERR_INVALID_ARG);
+  EXPECT(qjl_generation_step_devpos(&good, 128, 4, nullptr, P, P, P, P, PI, 4, P8, P16, P16, P8, P16, P16, PF, P, 1 << 20, nullptr) == QJL_ERR_INVALID_ARG);
+  EXPECT(qjl_generation_step_devpos(&good, 128, 4, PI, P, P, P, P, PI, 4, P8, P16, P16, P8, P16, P16, PF, P, 16, nullptr) == QJL_ERR_WORKSPACE);
+  EXPECT(qjl_generation_step_devpos(&good, 128, 3, PI, P, P, P, P, PI, 4, P8, P16, P16, P8, P16, P16, PF, P, 1 << 20, nullptr) == QJL_ERR_UNSUPPORTED);
   EXPECT(qjl_select_outliers(&good, P, 17, PI, P, 1 << 20, nullptr) == QJL_ERR_INVALID_ARG);
   EXPECT(qjl_select_outliers(&good, P, 4, PI, P, 0, nullptr) == QJL_ERR_WORKSPACE);
   EXPECT(qjl_make_dual_sketch(&good, 0, P, P, PI, 4, P, nullptr) == QJL_ERR_INVALID_ARG);

@@ -33,7 +33,7 @@ def test_header_symbols_are_exported(L):
     assert names == ["qjl_append_keys", "qjl_decode_attention", "qjl_decode_attention_dual",
                      "qjl_decode_attention_dual_vq", "qjl_decode_attention_noalloc", "qjl_decode_attention_splits", "qjl_decode_attention_timed",
                      "qjl_decode_attention_vq", "qjl_decode_dual_workspace_bytes", "qjl_decode_noalloc_max_bytes", "qjl_decode_plan", "qjl_decode_step",
-                     "qjl_decode_workspace_bytes", "qjl_generation_step",
+                     "qjl_decode_workspace_bytes", "qjl_generation_step", "qjl_generation_step_devpos",
                      "qjl_make_dual_sketch", "qjl_make_sketch", "qjl_make_sketch_orthogonal", "qjl_outlier_workspace_bytes",
                      "qjl_project_query", "qjl_quantize_keys", "qjl_quantize_keys_dual", "qjl_quantize_values",
                      "qjl_scores", "qjl_select_outliers", "qjl_status_string", "qjl_version"]

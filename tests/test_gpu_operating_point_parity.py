@@ -170,6 +170,81 @@ def test_generation_steps_stream_into_the_caches():
     assert float((dc[0][:, :, :e] != bulk_b).float().mean()) < 1e-3
 
 
+def test_generation_loop_replayed_from_a_graph():
+    """The step with its position in device memory (qjl_generation_step_devpos), recorded once into a HIP graph
+    together with the increment of the position and replayed for 40 tokens, with eager work (the next token's
+    inputs, the comparison) and synchronizations between the replays: every replay against the oracle's stream.
+    The capacity is cut into three chunks of 512 rows and the loop starts at row 1000, so the last chunk is empty
+    for the first 24 steps and takes the new rows after that."""
+    dt, B, Hq, Hkv, cap, m, m_out, vbits, scale = "bf16", 1, 8, 2, 1400, 256, 128, 4, 0.0884
+    p = _problem(dt, B, Hq, Hkv, cap, m, m_out, 2323)
+    say("[generation graph] 40 replays from position 1000")
+    assert qjl.qjl_decode_plan(B, Hq, Hkv, cap, 128, m, m_out)[2:] == (3, 512)
+    start, steps = 1000, 40
+    ob, oi, oo, _, _ = orc.quantize_keys_dual(p["K64"][:, :, :start], p["S_in64"], p["S_out64"], p["ch"])
+    oc, os_, oz = orc.quantize_values(p["V64"][:, :, :start], vbits)
+    shapes = [((m + m_out) // 8, np.uint8), (None, np.float16), (None, np.float16), (128 * vbits // 8, np.uint8), (None, np.float16), (None, np.float16)]
+    host = []
+    for (last, tp), first in zip(shapes, (ob, oi, oo, oc, os_, oz)):
+        full = np.full((B, Hkv, cap) + ((last,) if last else ()), 9, dtype=tp)     # stale contents behind the rows in use
+        full[:, :, :start] = first
+        host.append(full)
+    ref_caches = [x.copy() for x in host]
+    dc = [_dev(x) for x in host]
+    ch_d = _dev(p["ch"].astype(np.int32))
+    ws = torch.empty((qjl.qjl_decode_dual_workspace_bytes(B, Hq, Hkv, cap, 128, m, m_out),), dtype=torch.uint8, device=DEV)
+    out = torch.empty((B, Hq, 128), dtype=torch.float32, device=DEV)
+    Qs = torch.empty((B, Hq, 128), dtype=DT[dt], device=DEV)
+    Kn = torch.empty((B, Hkv, 1, 128), dtype=DT[dt], device=DEV)
+    Vn = torch.empty((B, Hkv, 1, 128), dtype=DT[dt], device=DEV)
+    pos_t = torch.tensor([start], dtype=torch.int32, device=DEV)
+
+    def feed(pos):
+        Qs.copy_(inputs.make_normal((B, Hq, 128), DT[dt], 9000 + pos, DEV))
+        Kn.copy_(p["K"][:, :, pos:pos + 1])
+        Vn.copy_(p["V"][:, :, pos:pos + 1])
+
+    def step():
+        qjl.qjl_generation_step(Qs, Kn, Vn, p["S_dual"], ch_d, *dc, pos_t, m_out, vbits, scale, out=out, workspace=ws)
+        pos_t.add_(1)
+
+    feed(start)
+    step()                                            # once eagerly (what it writes to row `start` the first replay writes again)
+    pos_t.fill_(start)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    pos_t.fill_(start)
+    worst = 0.0
+    for pos in range(start, start + steps):
+        feed(pos)
+        g.replay()
+        torch.cuda.synchronize()
+        ref = orc.generation_step(inputs.to_f64(Qs), p["S_in64"], p["S_out64"], p["ch"], *ref_caches,
+                                  p["K64"][:, :, pos:pos + 1], p["V64"][:, :, pos:pos + 1], pos, vbits, scale)
+        err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref)))
+        assert err <= 2e-3, (pos, err)
+        worst = max(worst, err)
+        assert int(pos_t.item()) == pos + 1
+    say(f"  worst error over the replays {worst:.3g}")
+    e = start + steps
+    bulk_c, bulk_s, bulk_z = qjl.qjl_quantize_values(p["V"][:, :, :e].contiguous(), vbits)
+    assert torch.equal(dc[3][:, :, :e], bulk_c) and torch.equal(dc[4][:, :, :e], bulk_s) and torch.equal(dc[5][:, :, :e], bulk_z)
+    assert torch.all(dc[3][:, :, e:] == 9)            # nothing behind the newest row was touched
+    # a position outside the caches cannot be reported from the kernel: it is clamped
+    for bad, used in ((cap + 5, cap - 1), (-3, 0)):
+        caches = [x.copy() for x in ref_caches]
+        dcc = [_dev(x) for x in caches]
+        feed(used)
+        pos_t.fill_(bad)
+        qjl.qjl_generation_step(Qs, Kn, Vn, p["S_dual"], ch_d, *dcc, pos_t, m_out, vbits, scale, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        ref = orc.generation_step(inputs.to_f64(Qs), p["S_in64"], p["S_out64"], p["ch"], *caches,
+                                  p["K64"][:, :, used:used + 1], p["V64"][:, :, used:used + 1], used, vbits, scale)
+        assert float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - ref))) <= 2e-3, bad
+
+
 def test_unsupported_combinations_are_reported():
     L = qjl.lib()
     x = torch.zeros(4096, dtype=torch.uint8, device=DEV)
