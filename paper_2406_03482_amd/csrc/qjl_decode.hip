@@ -578,10 +578,11 @@ decode_kernel(decode_args a) {
     // block every lane re-reads row 0 of the current one, a single cached line.
     const int kb_next = have_next ? kn : k0;
     const int lim_next = have_next ? k_end - 1 - kn : 0;
-    // Four-head groups: the two waves of a SIMD both keep the vector ALU busy most of the time.  The one
-    // that is in its value pass -- the pass that issues the loads -- goes first (measured: 8192 keys x 16 x
-    // 8 kv heads 55.9 -> 54.9 us, with 4-bit values 43.6 -> 40.8 us; one-head groups do not change).
-    if constexpr (GT == 4) __builtin_amdgcn_s_setprio(1);
+    // Groups of two and four heads: the two waves of a SIMD both keep the vector ALU busy most of the time.
+    // The one that is in its value pass -- the pass that issues the loads -- goes first (measured: 8192 keys
+    // x 16 x 8 kv heads 55.9 -> 54.9 us, with 4-bit values 43.6 -> 40.8 us, with 384-bit codes as well,
+    // two heads at a time, 52.4 -> 48.9 us; one-head groups do not change).
+    if constexpr (GT >= 2) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] *= alpha;
     const PV* pw = reinterpret_cast<const PV*>(pbuf) + r * 16;
@@ -612,7 +613,7 @@ decode_kernel(decode_args a) {
       // all sixteen would need a second set of V registers
       __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (GT == 4) __builtin_amdgcn_s_setprio(0);
+    if constexpr (GT >= 2) __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
