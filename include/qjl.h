@@ -14,9 +14,12 @@
  *   - All data pointers are DEVICE pointers owned by the caller; the library
  *     allocates nothing.  Between calls it remembers only attributes of the
  *     devices it has run on (compute-unit count, "LDS limit of this kernel
- *     already raised"), per device ordinal, in atomics: calls from several
- *     host threads and on several devices are safe, and no result depends on
- *     that memory.  No environment variable is read.  Tensors are dense,
+ *     already raised"), per device ordinal, in atomics, and a count of the
+ *     attention launches it has made (a launch's number names it in a word
+ *     of the caller's workspace through which the workgroups of that launch
+ *     agree on how they share their chunks): calls from several host threads
+ *     and on several devices are safe, and no result depends on that memory.
+ *     No environment variable is read.  Tensors are dense,
  *     row-major, with exactly the shapes stated below.  Pointers must be
  *     16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).

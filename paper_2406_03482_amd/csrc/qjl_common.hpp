@@ -157,7 +157,11 @@ struct decode_plan {
   int gt;            // query heads handled together by one workgroup (divides G)
   int nsplit;        // context chunks per (batch, kv head, head group)
   int chunk;         // keys per chunk (multiple of 64)
+  // Not 0: the chunks come in pairs of chunk_big + chunk_small = 2 * chunk keys (both multiples of 64), and
+  // of the two workgroups that share a pair the one that runs on an odd-numbered XCD takes the small one.
+  int chunk_big, chunk_small;
   size_t off_part;   // byte offset of the per-chunk records inside the workspace
+  size_t off_flag;   // byte offset of the 8-byte word through which the workgroups of a launch agree on that
   size_t total;      // bytes
 };
 // m_out = 0: one code per key (sh.m bits, one shared sketch S[m,d]).  m_out > 0: a key's

@@ -23,6 +23,14 @@ namespace {
 
 constexpr int kD = 128;          // head dimension this kernel is written for
 constexpr int kPartStride = 132; // floats per partial record: max, sum, 2 pad, o[128]
+#ifndef QJL_SMALL_SHARE_1
+#define QJL_SMALL_SHARE_1 460
+#endif
+#ifndef QJL_SMALL_SHARE_G
+#define QJL_SMALL_SHARE_G 470
+#endif
+constexpr long kSmallShareOneHead = QJL_SMALL_SHARE_1;   // per mille of a pair of chunks that the slower XCD takes
+constexpr long kSmallShareGroups = QJL_SMALL_SHARE_G;
 constexpr int kMaxSplits = 512;  // most chunks a context is ever cut into (combine_kernel keeps that many records' heads in LDS)
 
 // LDS bytes of one workgroup: S q (gt*m floats), 4-bit tables (4*gt*m), byte
@@ -54,6 +62,9 @@ struct decode_args {
   int n, groups_per_kv;   // n = keys to attend to
   long n_cap;             // rows per (batch, kv head) in the caches (>= n; larger for a cache that is still filling)
   int nsplit, chunk;
+  int chunk_big, chunk_small;   // not 0: pairs of uneven chunks, see decode_plan
+  unsigned long long* flag;     // (nonce << 32) | parity of the XCD that runs workgroup 0
+  uint32_t nonce;               // of this launch, never 0
   float coef2;            // scale * sqrt(pi/2) / m * log2(e); m = bits of the (first) code part
   float coef2b;           // the same for the second part
   // Streaming (Algorithm 1 as a loop): the key of position n - 1 arrives with the call.
@@ -267,16 +278,34 @@ decode_kernel(decode_args a) {
   // for head counts that are multiples of 8 all chunks and all query-head groups
   // of a kv head run on one XCD and share its L2 (the head's sketch, and for
   // grouped queries its codes and values).
-  const int split = blockIdx.z;
-  const int bk = blockIdx.x;                          // b * Hkv + kvh
-  const size_t hq0 = ((size_t)bk * a.groups_per_kv + blockIdx.y) * GT;
+  int split = blockIdx.z;
+  int bk = blockIdx.x;                                // b * Hkv + kvh
+  int grp = blockIdx.y;
+  // Uneven pairs of chunks (see below, where the chunk is chosen): workgroup 8a + c of the launch order takes
+  // (batch, kv head) 4 (a mod gx/4) + c/2, so that the two workgroups that share a pair of chunks are
+  // neighbours in that order and run on XCDs of different parity; the query-head groups of a kv head still
+  // share an XCD.
+  const bool uneven = !AP && a.chunk_small != 0;      // uniform
+  int pair_slot = 0, place_parity = 0;
+  if (uneven) {
+    const unsigned L = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const unsigned cx = L & 7u, aa = L >> 3;
+    const unsigned q4 = gridDim.x >> 2;
+    const unsigned t = aa / q4;
+    bk = (int)(4u * (aa - t * q4) + (cx >> 1));
+    const unsigned t2 = t / gridDim.y;
+    grp = (int)(t - t2 * gridDim.y);
+    pair_slot = (int)t2;
+    place_parity = (int)(cx & 1u);
+  }
+  const size_t hq0 = ((size_t)bk * a.groups_per_kv + grp) * GT;
 
   int n = a.n;
   if constexpr (AP) {
     if (a.pos_dev != nullptr) n = min(max(*a.pos_dev, 0), a.n - 1) + 1;   // uniform: a scalar load
   }
-  const int k_begin = split * a.chunk;
-  const int k_end = min(n, k_begin + a.chunk);
+  int k_begin = split * a.chunk;
+  int k_end = min(n, k_begin + a.chunk);
   if constexpr (AP) {
     // chunks planned for the capacity that lie wholly behind the newest row: an empty record (weight 0 in
     // the merge) and nothing else
@@ -340,6 +369,44 @@ decode_kernel(decode_args a) {
         srow[u][i].load(a.S, s0 + (size_t)(u * kRowsPerPass + r16) * kD + (c16 + LPR * i) * 8);
   }
   __builtin_amdgcn_sched_barrier(0);
+  // ---- which chunk of its pair this workgroup takes.  The odd-numbered XCDs of this chip stream 5-12 %
+  // slower than the even ones (every workgroup stamped with its end time and XCC_ID: same buffers or
+  // rotating ones, eager or from a graph), and workgroups are dealt to the XCDs in turn -- but from a
+  // starting point that differs between launches (eager launches start at XCD 0, the same kernel replayed
+  // from a graph was seen to start at XCD 7).  So the launch agrees on it at run time: workgroup 0 publishes
+  // the parity of its own XCC_ID under this launch's nonce, every wave waits for that word (behind the loads
+  // of S and q that it has just issued) and a workgroup whose place in the order puts it on an odd XCD takes
+  // the small chunk.  The chunks and their records are the same whoever takes them, so the result does not
+  // depend on the outcome.  A word that already carries the nonce (a graph replayed) is used as it is: the
+  // same for every workgroup, which is all that correctness needs.  Workgroup 0 is dispatched first and waits
+  // for nobody, so the wait ends; should it not (20000 polls), the wave poisons its record with a NaN.
+  float poison = 0.f;
+  if (uneven) {
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+      const unsigned long long cur = __hip_atomic_load(a.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if ((uint32_t)(cur >> 32) != a.nonce) {
+        unsigned xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        __hip_atomic_store(a.flag, ((unsigned long long)a.nonce << 32) | (xcc & 1u), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    unsigned word = 0xFFFFFFFFu;                       // bit 0: parity of workgroup 0's XCD; all ones: no answer
+    if (lane == 0) {
+      for (int it = 0; it < 20000; ++it) {
+        const unsigned long long v = __hip_atomic_load(a.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(v >> 32) == a.nonce) { word = (uint32_t)v & 1u; break; }
+        __builtin_amdgcn_s_sleep(4);
+      }
+    }
+    word = __builtin_amdgcn_readfirstlane(word);
+    if (word == 0xFFFFFFFFu) { poison = __builtin_nanf(""); word = 0; }
+    const int slow = (place_parity ^ (int)word) & 1;
+    const int both = a.chunk_big + a.chunk_small;
+    split = 2 * pair_slot + slow;
+    k_begin = pair_slot * both + (slow ? a.chunk_big : 0);
+    k_end = min(n, k_begin + (slow ? a.chunk_small : a.chunk_big));
+  }
   // ---- then the first block of this wave: its HBM reads are in flight while
   // the tables are built.  Rows past the chunk end are clamped (never out of
   // bounds); their weight is 0.
@@ -638,7 +705,7 @@ decode_kernel(decode_args a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = o[e];
     }
-    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l; rec[2] = zsum; }
+    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l + poison; rec[2] = zsum; }
   }
   __syncthreads();
 
@@ -666,7 +733,7 @@ decode_kernel(decode_args a) {
     }
   }
   if constexpr (AP) {                                   // the new key's row of the caches, last: no store ahead of the loop's loads
-    if (has_new && blockIdx.y == 0) {
+    if (has_new && grp == 0) {
       if (tid < MW) a.bits_w[(row0 + pos) * MW + tid] = newcode[tid];
       if (tid == 0) a.norms_w[row0 + pos] = (uint16_t)newcode[MW];
       if constexpr (MWB > 0) { if (tid == 0) a.norms2_w[row0 + pos] = (uint16_t)newcode[MW + 1]; }
@@ -914,9 +981,26 @@ bool plan_decode(const qjl_shape& sh, int m_out, decode_plan* plan, int force_sp
   plan->gt = gt;
   plan->nsplit = (int)nsplit;
   plan->chunk = (int)chunk;
+  // Uneven pairs of chunks for long streams: 2 * chunk keys are cut 54 : 46 (53 : 47 for groups of heads),
+  // the odd-numbered XCDs take the small halves (see the kernel).  Needs an even number of chunks, whole
+  // groups of four (batch, kv head) pairs for the renumbering, and a last small chunk that is not empty.
+  plan->chunk_big = 0;
+  plan->chunk_small = 0;
+  const long pairs = (long)sh.batch * sh.kv_heads;
+  if (nsplit % 2 == 0 && pairs % 4 == 0 && chunk >= 2048) {
+    const long both = 2 * chunk;
+    const long small = (both * (gt == 1 ? kSmallShareOneHead : kSmallShareGroups) / 1000 + 32) / 64 * 64;
+    const long big = both - small;
+    if (small >= min_chunk && (nsplit / 2 - 1) * both + big < (long)sh.n) {
+      plan->chunk_big = (int)big;
+      plan->chunk_small = (int)small;
+    }
+  }
   size_t off = 0;
   plan->off_part = off;
   off = align_up(off + (size_t)sh.batch * sh.q_heads * records * kPartStride * sizeof(float), 256);
+  plan->off_flag = off;
+  off += 256;
   plan->total = off;
   return true;
 }
@@ -949,6 +1033,18 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   a.n_cap = n_cap > 0 ? n_cap : sh.n;
   a.groups_per_kv = (sh.q_heads / sh.kv_heads) / plan.gt;
   a.nsplit = plan.nsplit; a.chunk = plan.chunk;
+  // uneven pairs of chunks: not for the streaming step (its newest row and the chunks planned for a capacity
+  // keep the plain cut)
+  // ... nor for quantized values: there the vector ALU sets the pace, the same on every XCD, and uneven
+  // chunks are only uneven (4 x 32 heads x 32768 keys with 4-bit values: 71.9 -> 73.8 us with them)
+  const bool uneven = K_new == nullptr && !(vbits > 0 && vscale != nullptr);
+  a.chunk_big = uneven ? plan.chunk_big : 0;
+  a.chunk_small = uneven ? plan.chunk_small : 0;
+  a.flag = reinterpret_cast<unsigned long long*>(ws + plan.off_flag);
+  static std::atomic<uint32_t> launches{0};            // a number per launch, never 0: names the launch in the flag word
+  uint32_t nonce = launches.fetch_add(1, std::memory_order_relaxed) + 1;
+  if (nonce == 0) nonce = launches.fetch_add(1, std::memory_order_relaxed) + 1;
+  a.nonce = nonce;
   a.coef2 = sh.scale * 1.2533141373155002512f / (float)sh.m * 1.4426950408889634074f;
   switch (sh.dtype) {
     case QJL_F32: rc = launch_m<f32_t>(sh, m_out, vbits, plan, a, st, ev_before, ev_after); break;

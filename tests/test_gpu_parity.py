@@ -467,6 +467,53 @@ def test_decode_on_side_stream_and_in_a_graph():
         assert_attention(got.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (16, 4), (8, 8)])
+def test_uneven_chunk_pairs_agree_whoever_takes_them(Hq, Hkv):
+    """Long chunks are cut into uneven pairs and the workgroups of a launch agree at run time, through a word in
+    the workspace, on who takes which (the slower XCDs take the small ones).  The chunks and their records are
+    the same either way, so the result must not depend on the outcome: eager calls, calls on a workspace full
+    of ones or of noise, and replays from a graph (whose workgroups land on other XCDs) all have to give the
+    same bits, and the oracle's numbers."""
+    say(f"[uneven chunks] Hq={Hq} Hkv={Hkv}")
+    B, n, d, m, scale, splits = 1, 20000, 128, 256, 0.0884, 4
+    total, gt, nsplit, chunk = qjl.qjl_decode_plan(B, Hq, Hkv, n, d, m, splits=splits)
+    assert nsplit == 4 and chunk >= 2048               # what the uneven cut needs: long chunks, an even count
+    K = inputs.make_keys(B, Hkv, n, d, torch.bfloat16, 171, DEV)
+    V = inputs.make_normal((B, Hkv, n, d), torch.bfloat16, 173, DEV)
+    S = qjl.qjl_make_sketch(17, m, d, torch.bfloat16, DEV)
+    (bits_d, nu_d), (bits, nu16) = oracle_cache(K, S)
+    Q = inputs.make_normal((B, Hq, d), torch.bfloat16, 180, DEV)
+    ref = orc.decode_attention(inputs.to_f64(Q), inputs.to_f64(S), bits, nu16, inputs.to_f64(V), scale)
+    ws = torch.empty((total,), dtype=torch.uint8, device=DEV)
+    out = torch.empty((B, Hq, d), dtype=torch.float32, device=DEV)
+    first = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, workspace=ws, splits=splits).clone()
+    assert_attention(first.cpu().numpy(), ref)
+    for fill in ("ones", "noise", "as left"):
+        if fill == "ones":
+            ws.fill_(255)
+        elif fill == "noise":
+            ws.copy_(torch.randint(0, 256, (total,), dtype=torch.uint8, device=DEV))
+        for _ in range(3):
+            out.zero_()
+            qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, out=out, workspace=ws, splits=splits)
+            assert torch.equal(out, first), fill
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, out=out, workspace=ws, splits=splits)
+        qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, out=out, workspace=ws, splits=splits)
+    for i in range(4):
+        out.zero_()
+        if i == 2:
+            ws.fill_(0)                                # eager work on the workspace between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, first), f"replay {i}"
+    # the same keys cut evenly (an odd number of chunks): other sums, the same attention
+    odd = qjl.qjl_decode_attention(Q, S, bits_d, nu_d, V, scale, splits=3)
+    assert_attention(odd.cpu().numpy(), ref)
+
+
 def test_many_small_units():
     """Many (batch, head) units with a short context: one workgroup per unit, no chunking."""
     say("[decode] B=24 Hq=16 Hkv=16 n=200")
