@@ -240,7 +240,9 @@ template <> struct vtile_q<8> {
 // per token (Section 3.2).  o = sum_j p_j (zero_j + scale_j c_j): the weight
 // that goes to the value pass is p_j scale_j, and sum_j p_j zero_j, the same for
 // every channel, is carried next to the softmax denominator.
-template <typename T, int GT, int MW, int MWB, int VB, bool AP>
+// UN: uneven pairs of chunks shared out by XCD parity (a kernel of its own: the steps it adds to the prologue
+// are not free for short contexts -- as a run-time branch they cost 4096 keys x 32 heads 9.3 -> 10.7 us).
+template <typename T, int GT, int MW, int MWB, int VB, bool AP, bool UN = false>
 __global__ void __launch_bounds__(decode_waves(GT, MW * 32, T::bytes, VB > 0) * 64,
                                   (T::bytes == 4 || GT == 4) ? 1 : (decode_waves(GT, MW * 32, 2, VB > 0) == 4 && GT == 1) ? 4 : 2)
 decode_kernel(decode_args a) {
@@ -285,9 +287,8 @@ decode_kernel(decode_args a) {
   // (batch, kv head) 4 (a mod gx/4) + c/2, so that the two workgroups that share a pair of chunks are
   // neighbours in that order and run on XCDs of different parity; the query-head groups of a kv head still
   // share an XCD.
-  const bool uneven = !AP && a.chunk_small != 0;      // uniform
   int pair_slot = 0, place_parity = 0;
-  if (uneven) {
+  if constexpr (UN) {
     const unsigned L = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     const unsigned cx = L & 7u, aa = L >> 3;
     const unsigned q4 = gridDim.x >> 2;
@@ -381,7 +382,7 @@ decode_kernel(decode_args a) {
   // same for every workgroup, which is all that correctness needs.  Workgroup 0 is dispatched first and waits
   // for nobody, so the wait ends; should it not (20000 polls), the wave poisons its record with a NaN.
   float poison = 0.f;
-  if (uneven) {
+  if constexpr (UN) {
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
       const unsigned long long cur = __hip_atomic_load(a.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if ((uint32_t)(cur >> 32) != a.nonce) {
@@ -705,7 +706,11 @@ decode_kernel(decode_args a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) rec[4 + c * 8 + e] = o[e];
     }
-    if (lane == 0) { rec[0] = m_run[g]; rec[1] = l + poison; rec[2] = zsum; }
+    if (lane == 0) {
+      rec[0] = m_run[g];
+      if constexpr (UN) rec[1] = l + poison; else rec[1] = l;
+      rec[2] = zsum;
+    }
   }
   __syncthreads();
 
@@ -801,7 +806,7 @@ __global__ void __launch_bounds__(2 * kD) combine_kernel(const float* __restrict
   if (half == 0) out[head * kD + ch] = (O + s_o[ch] + Zc + s_zsum) / (L + s_lsum);
 }
 
-template <typename T, int GT, int MW, int MWB, int VB, bool AP>
+template <typename T, int GT, int MW, int MWB, int VB, bool AP, bool UN = false>
 int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
   static std::atomic<uint64_t> lds_set{0};             // per kernel instantiation: devices whose limit is raised
@@ -810,22 +815,33 @@ int launch_t(const qjl_shape& sh, const decode_plan& plan, decode_args a, hipStr
   // value row: 128 codes as floats, scale, zero point, up to 128 packed bytes
   const size_t lds = decode_lds_bytes(GT, MW * 32) +
                      (AP ? (MW * 32 + 2 + MW + 2 + (VB > 0 ? kD + 2 + 32 : 0) + 2) * sizeof(float) : 0);
-  int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP>), lds, lds_set);
+  int rc_lds = allow_dynamic_lds(reinterpret_cast<const void*>(&decode_kernel<T, GT, MW, MWB, VB, AP, UN>), lds, lds_set);
   if (rc_lds != QJL_OK) return rc_lds;
   const long pairs = (long)sh.batch * sh.kv_heads;
   if (a.groups_per_kv > 65535 || plan.nsplit > 65535 || pairs > 0x7FFFFFFFL) return QJL_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)pairs, (unsigned)a.groups_per_kv, (unsigned)plan.nsplit);
   if (ev0 || ev1)   // the events take the kernel's own start and stop timestamps
-    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP>), grid, dim3(kNW * 64), (uint32_t)lds, st,
+    hipExtLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP, UN>), grid, dim3(kNW * 64), (uint32_t)lds, st,
                           ev0, ev1, 0u, a);
   else
-    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP>), grid, dim3(kNW * 64), lds, st, a);
+    hipLaunchKernelGGL((decode_kernel<T, GT, MW, MWB, VB, AP, UN>), grid, dim3(kNW * 64), lds, st, a);
   return launch_status();
 }
 
 template <typename T, int MW, int MWB, int VB = 0, bool AP = false>
 int launch_g(const qjl_shape& sh, const decode_plan& plan, const decode_args& a, hipStream_t st,
              hipEvent_t ev0, hipEvent_t ev1) {
+  // uneven pairs of chunks: 16-bit types, one-part codes, unquantized values, not the streaming step (two-part
+  // codes measured no gain: 185.3 us either way for 4 x 32 heads x 32768 keys on 384 bits)
+  if constexpr (T::bytes == 2 && MWB == 0 && VB == 0 && !AP) {
+    if (a.chunk_small != 0) {
+      switch (plan.gt) {
+        case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VB, AP, true>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+        case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VB, AP, true>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
+        default: return launch_t<T, 1, MW, MWB, VB, AP, true>(sh, plan, a, st, ev0, ev1);
+      }
+    }
+  }
   switch (plan.gt) {
     case 4: if constexpr (MW * 32 * 4 <= 1024) return launch_t<T, 4, MW, MWB, VB, AP>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
     case 2: if constexpr (MW * 32 * 2 <= 1024) return launch_t<T, 2, MW, MWB, VB, AP>(sh, plan, a, st, ev0, ev1); else return QJL_ERR_UNSUPPORTED;
@@ -1037,7 +1053,7 @@ int launch_decode(const qjl_shape& sh, int m_out, const decode_plan& plan, const
   // keep the plain cut)
   // ... nor for quantized values: there the vector ALU sets the pace, the same on every XCD, and uneven
   // chunks are only uneven (4 x 32 heads x 32768 keys with 4-bit values: 71.9 -> 73.8 us with them)
-  const bool uneven = K_new == nullptr && !(vbits > 0 && vscale != nullptr);
+  const bool uneven = K_new == nullptr && !(vbits > 0 && vscale != nullptr) && m_out == 0 && sh.dtype != QJL_F32;
   a.chunk_big = uneven ? plan.chunk_big : 0;
   a.chunk_small = uneven ? plan.chunk_small : 0;
   a.flag = reinterpret_cast<unsigned long long*>(ws + plan.off_flag);
